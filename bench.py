@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-free KV transfer hot path on one MI355X.
+
+One step = build the copy plan (kvx_plan: host validation, one H2D copy, scan
+and fill kernels), gather the batch's KV out of the sender's paged pool into
+the contiguous buffer (kvx_pack), scatter it into the receiver's paged pool
+(kvx_unpack).  Inputs are resident in HBM before the timed region.  Prints ONE
+JSON line.  Synthetic workload 2 (Llama-3-8B-shaped KV, 16 requests of
+1024..4096 tokens, 128-token pages, scattered block tables) unless --workload
+says otherwise.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
+
+
+class Setup:
+    """Device-resident inputs and outputs of one workload."""
+
+    def __init__(self, idx: int, with_dst: bool = True, with_buf: bool = True, fill: bool = True):
+        import torch
+        from paper_2408_08147_amd import kvx, workloads as W
+        self.torch, self.kvx, self.W = torch, kvx, W
+        kvx.load()
+        self.w = w = W.CONFIGS[idx]
+        self.batch = b = W.draw_batch(w)
+        self.dev = torch.device("cuda:0")
+        self.stream = torch.cuda.Stream(device=self.dev)
+        self.sp = kvx.pool_desc(w.num_layers, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_s,
+                                b.num_pages_s, w.layout_s)
+        self.dp = kvx.pool_desc(w.num_layers, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_d,
+                                b.num_pages_d, w.layout_d)
+        self.sb = kvx.BatchDesc(b.seq_lens, b.ids_s, b.offs_s)
+        self.db = kvx.BatchDesc(b.seq_lens, b.ids_d, b.offs_d)
+        self.ws_bytes = kvx.kvx_plan_workspace_bytes(self.sp, self.sb, self.dp, self.db)
+        self.bpt = w.num_layers * 2 * w.row_bytes
+        self.payload = self.bpt * b.total_tokens
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
+        self.src = torch.empty(self.sp.dense_bytes, dtype=torch.uint8, device=self.dev)
+        if fill:
+            W.fill_values_torch(w.value_kind, self.src, w.seed)
+        self.dst = torch.full((self.dp.dense_bytes,), 0xC3, dtype=torch.uint8, device=self.dev) if with_dst else None
+        self.buf = torch.empty(self.payload, dtype=torch.uint8, device=self.dev) if with_buf else None
+        torch.cuda.synchronize()
+
+    def plan(self, l0=0, l1=None, launch=None):
+        l1 = self.w.num_layers if l1 is None else l1
+        p = self.kvx.kvx_plan(self.sp, self.sb, self.dp, self.db, l0, l1, self.ws.data_ptr(), self.ws_bytes,
+                              self.stream.cuda_stream)
+        if launch:
+            self.kvx.kvx_plan_set_launch(p, **launch)
+        return p
+
+    def pack(self, p):
+        self.kvx.kvx_pack(p, self.src.data_ptr(), self.buf.data_ptr(), self.payload, self.stream.cuda_stream)
+
+    def unpack(self, p):
+        self.kvx.kvx_unpack(p, self.buf.data_ptr(), self.payload, self.dst.data_ptr(), self.stream.cuda_stream)
+
+    def convert(self, p):
+        self.kvx.kvx_convert(p, self.src.data_ptr(), self.dst.data_ptr(), self.stream.cuda_stream)
+
+    def time_op(self, fn, iters=10, warmup=2):
+        """Mean milliseconds per call of fn() by events on the library's stream."""
+        torch = self.torch
+        for _ in range(warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(self.stream)
+        for _ in range(iters):
+            fn()
+        e1.record(self.stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+
+def cpu_baseline(setup: Setup, target_bytes: float = 1.5e9):
+    """Times the CPU oracle (pack + unpack) on the first few layers of the same
+    workload, copied off the device, and checks the GPU result against it."""
+    import numpy as np
+    from oracle import kvxo
+    w, b = setup.w, setup.batch
+    per_layer = 2 * w.row_bytes * b.total_tokens
+    layers = int(max(1, min(w.num_layers, target_bytes // per_layer)))
+    assert w.layout_s == 0 and w.layout_d == 0, "sample by leading layers needs layer-major pools"
+    slab_s = 2 * b.num_pages_s * w.page_s * w.row_bytes
+    slab_d = 2 * b.num_pages_d * w.page_d * w.row_bytes
+    src = setup.src[: layers * slab_s].cpu().numpy()
+    ps = kvxo.Pool(layers, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_s, b.num_pages_s, 0)
+    pd = kvxo.Pool(layers, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_d, b.num_pages_d, 0)
+    bs, bd = kvxo.Batch(b.seq_lens, b.ids_s, b.offs_s), kvxo.Batch(b.seq_lens, b.ids_d, b.offs_d)
+    total = kvxo.total_bytes(ps, bs, 0, layers)
+    cores = len(os.sched_getaffinity(0))
+    cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+    out = {}
+    buf = np.empty(total, dtype=np.uint8)
+    dst = np.full(layers * slab_d, 0xC3, dtype=np.uint8)
+    for label, th in (("threads_1", 1), ("all", cores)):
+        buf[:] = 0
+        t0 = time.perf_counter()
+        kvxo.pack(ps, bs, 0, layers, src, buf, threads=th)
+        t1 = time.perf_counter()
+        kvxo.unpack(pd, bd, 0, layers, buf, dst, threads=th)
+        t2 = time.perf_counter()
+        out[label] = dict(pack_s=t1 - t0, unpack_s=t2 - t1, gbps=2 * total / (t2 - t0) / 1e9)
+    # bonus parity at full shape: the GPU's result for these layers, through its own full-range plan
+    plan = setup.plan()
+    setup.dst.fill_(0xC3)
+    setup.pack(plan)
+    setup.unpack(plan)
+    setup.stream.synchronize()
+    got_dst = setup.dst[: layers * slab_d].cpu().numpy()
+    ok = bool(np.array_equal(got_dst, dst))
+    gbuf = setup.buf.cpu().numpy()
+    for r in range(w.num_requests):
+        for l in (0, layers - 1):
+            o, n = setup.kvx.kvx_plan_segment(plan, r, l)
+            oo, nn = kvxo.segment(ps, bs, 0, layers, r, l)
+            ok = ok and n == nn and bool(np.array_equal(gbuf[o:o + n], buf[oo:oo + nn]))
+    plan.destroy()
+    return {
+        "value": round(out["all"]["gbps"], 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+        "sample": f"pack+unpack of layers [0,{layers}) of the same batch ({total / 1e9:.2f} GB payload), "
+                  f"moved bytes = 2*payload",
+        "value_1_thread": round(out["threads_1"]["gbps"], 3),
+        "us_per_request": round((out["all"]["pack_s"] + out["all"]["unpack_s"]) * 1e6 / w.num_requests
+                                * (w.num_layers / layers), 1),
+        "gpu_matches_oracle_on_sample": ok,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this path runs on one GPU (no collectives, no sharding); use --gpus 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    s = Setup(args.workload)
+    kvx, w = s.kvx, s.w
+    K, Wm = args.steps, args.warmup
+
+    def step(events=None):
+        p = s.plan()
+        if events is not None:
+            events[0].record(s.stream)
+        s.pack(p)
+        if events is not None:
+            events[1].record(s.stream)
+        s.unpack(p)
+        if events is not None:
+            events[2].record(s.stream)
+        p.destroy()
+
+    for _ in range(Wm):
+        step()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        step(evs[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / K
+    pack_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / K
+    unpack_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / K
+
+    # outside the step: plan alone (host + device part), convert pool to pool, plain D2D copy ceiling
+    t2 = time.perf_counter()
+    for _ in range(20):
+        s.plan().destroy()
+    s.stream.synchronize()
+    plan_ms = (time.perf_counter() - t2) * 1e3 / 20
+    p = s.plan()
+    convert_ms = s.time_op(lambda: s.convert(p), iters=5, warmup=1)
+    p.destroy()
+    half = s.payload // 2 // 256 * 256
+    with torch.cuda.stream(s.stream):
+        memcpy_ms = s.time_op(lambda: s.buf[:half].copy_(s.buf[half:2 * half]), iters=5, warmup=1)
+
+    dom_name, dom_ms = ("kvx_pack", pack_ms) if pack_ms >= unpack_ms else ("kvx_unpack", unpack_ms)
+    achieved = 2 * s.payload / (dom_ms * 1e-3) / 1e9
+    moved = 2 * s.payload / (ms_step * 1e-3) / 1e9
+    R = w.num_requests
+    out = {
+        "metric": "kv_pack_unpack_moved", "value": round(moved, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"{s.w.index}:{w.name}", "layers": w.num_layers, "kv_heads": w.num_kv_heads,
+                   "head_dim": w.head_dim, "elem_bytes": w.elem_bytes, "page_tokens": w.page_s,
+                   "requests": R, "total_tokens": s.batch.total_tokens, "payload_bytes": s.payload,
+                   "step": "kvx_plan + kvx_pack + kvx_unpack"},
+        "hbm_frac_pair": round(4 * s.payload / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "us_per_request": round(ms_step * 1e3 / R, 2), "requests_per_s": round(R / (ms_step * 1e-3), 1),
+        "ops": {"plan_ms": round(plan_ms, 4), "pack_ms": round(pack_ms, 4), "unpack_ms": round(unpack_ms, 4),
+                "convert_ms": round(convert_ms, 4),
+                "pack_hbm_GBps": round(2 * s.payload / pack_ms / 1e6, 1),
+                "unpack_hbm_GBps": round(2 * s.payload / unpack_ms / 1e6, 1),
+                "convert_hbm_GBps": round(2 * s.payload / convert_ms / 1e6, 1),
+                "torch_d2d_copy_hbm_GBps": round(2 * half / memcpy_ms / 1e6, 1)},
+        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(s)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

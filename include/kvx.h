@@ -1,0 +1,209 @@
+/*
+ * kvx -- block-free KV-cache transfer between paged pools on AMD MI355X (gfx950).
+ *
+ * The operations follow section 3.6 of "P/D-Serve: Serving Disaggregated Large
+ * Language Model at Scale" (arXiv 2408.08147), "Block-free D2D KVCache
+ * Transfer": the sender gathers a request's KV cache out of its discrete
+ * fixed-size blocks into one contiguous byte buffer (kvx_pack), the bytes
+ * travel as a whole, and the receiver restores its own discrete blocks from
+ * them (kvx_unpack, the paper's RecvScatter).  kvx_convert does both in one
+ * pass when the two pools are on one device.  The buffer itself stands in for
+ * the wire.
+ *
+ * Conventions for every call
+ *   - Plain C ABI.  Pointers marked [host] are host memory, [device] are device
+ *     memory of the current HIP device.  `stream` is a hipStream_t passed as
+ *     void* (NULL = the null stream).
+ *   - The caller owns all device memory: pools, buffer and the plan workspace.
+ *     The library owns only the host-side plan object.  Host arrays handed to
+ *     kvx_plan are copied before it returns.
+ *   - pack / unpack / convert enqueue work on `stream` and return; they never
+ *     synchronise and never allocate device memory.
+ *   - Every call returns a kvx_status; nothing aborts or throws.  All argument,
+ *     geometry and block-table checks happen on the host inside kvx_plan, and a
+ *     plan that fails leaves the workspace untouched.
+ *   - Results are bit-exact copies and do not depend on the launch configuration.
+ *
+ * Memory model (where the paper is silent, these are this library's readings)
+ *   - A token row is the contiguous bytes [head][dim] of one token, one layer,
+ *     K or V:  row = num_kv_heads * head_dim * elem_bytes.  row, every stride
+ *     and every base pointer must be a multiple of 16 bytes.
+ *   - A pool addresses a row as
+ *         layer*stride_layer + kv*stride_kv + page*stride_page + slot*stride_token
+ *     with kv = 0 for K, 1 for V.
+ *   - The buffer of a plan over layers [l0,l1) holds the requests in batch order
+ *     with no padding; inside a request the layers ascend, each layer is all K
+ *     rows then all V rows, tokens ascending ("one after another").  With
+ *     T_r = tokens of all earlier requests, n_r = tokens of request r and
+ *     bpt = (l1-l0)*2*row:
+ *         offset(r, l, kv, t) = T_r*bpt + (((l-l0)*2 + kv)*n_r + t)*row
+ *   - Slots of a request's last page beyond n_r are neither read nor written.
+ *     Block-table entries beyond ceil(n_r/page_tokens) are ignored.
+ */
+#ifndef KVX_H
+#define KVX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KVX_OK = 0,
+    KVX_ERR_INVALID_ARG = 1, /* NULL where not allowed, zero sizes, bad layer range, sides that disagree */
+    KVX_ERR_ALIGNMENT = 2,   /* row, a stride or a pointer is not a multiple of 16 bytes */
+    KVX_ERR_BLOCK_TABLE = 3, /* page id outside the pool, too few pages for a length, a receiver page
+                                listed twice, CSR offsets not ascending */
+    KVX_ERR_CAPACITY = 4,    /* buffer or workspace too small */
+    KVX_ERR_UNSUPPORTED = 5, /* a size beyond what the kernels index (see kvx_plan) */
+    KVX_ERR_DEVICE = 6       /* a HIP call failed; hipGetLastError has the detail */
+} kvx_status;
+
+typedef enum {
+    KVX_LAYOUT_LAYER_MAJOR = 0, /* [layer][K,V][page][token][head][dim] */
+    KVX_LAYOUT_PAGE_MAJOR = 1   /* [page][layer][K,V][token][head][dim] */
+} kvx_layout;
+
+/* Geometry of one paged pool (section 2.2.3, "Block-fixed Management": device
+ * memory organised as discrete blocks of fixed size).  The base pointer is
+ * passed per call.  If all four strides are 0 they are derived from `layout`
+ * for a dense pool; otherwise all four must be given (bytes) and `layout` is
+ * ignored. */
+typedef struct {
+    uint32_t num_layers;
+    uint32_t num_kv_heads; /* this device's share of the heads */
+    uint32_t head_dim;
+    uint32_t elem_bytes;   /* bytes per KV element; the element type is opaque */
+    uint32_t page_tokens;  /* tokens per page (block) */
+    uint32_t num_pages;    /* pages in the pool */
+    uint32_t layout;       /* kvx_layout */
+    uint32_t reserved;     /* must be 0 */
+    uint64_t stride_layer, stride_kv, stride_page, stride_token;
+} kvx_pool_desc;
+
+/* A batch of requests on one side: lengths and CSR block tables.
+ * block_ids[block_offsets[r] .. block_offsets[r+1]) are the physical pages of
+ * request r in logical order.  All three arrays are [host]. */
+typedef struct {
+    uint32_t num_requests;
+    uint32_t reserved;             /* must be 0 */
+    const uint32_t *seq_lens;      /* [R] tokens per request; 0 is allowed */
+    const uint32_t *block_ids;     /* [block_offsets[R]] */
+    const uint64_t *block_offsets; /* [R+1], ascending, block_offsets[0] == 0 */
+} kvx_batch_desc;
+
+/* Launch configuration of the copy kernels.  Zero in a field = library default.
+ * It changes speed only, never results. */
+typedef struct {
+    uint32_t unroll;        /* 16-byte loads in flight per lane before the first store: 1,2,4,8 */
+    uint32_t nontemporal;   /* 1 = off, 2 = non-temporal loads and stores */
+    uint32_t order;         /* 1 = (layer,kv) outermost, 2 = copy run outermost */
+    uint32_t xcd_swizzle;   /* 1 = off, 2 = give each of the 8 XCDs a contiguous range of tiles */
+    uint32_t max_workgroups;/* cap on the grid; tiles beyond it are taken in a grid-stride loop */
+    uint32_t reserved[3];
+} kvx_launch_cfg;
+
+typedef struct kvx_plan_s kvx_plan_t;
+
+/* One record of the flat copy plan in the device workspace: a maximal span of
+ * tokens of one request that is contiguous on both sides.  The same record
+ * serves every (layer, kv) of the plan's range. */
+typedef struct {
+    uint64_t src_off; /* pool side: page*stride_page + slot*stride_token; buffer side: T_r*bpt + t*row */
+    uint64_t dst_off; /* likewise for the destination */
+    uint32_t bytes;   /* tokens in the run * row */
+    uint32_t seq_len; /* n_r of the owning request */
+    uint32_t request; /* r */
+    uint32_t token;   /* first token of the run */
+} kvx_run;
+
+/* Where kvx_plan put its device tables inside the workspace (byte offsets from
+ * the workspace base; counts in records).  For inspection and tests. */
+typedef struct {
+    uint64_t token_prefix_off;                 /* uint64[R+1]: T_r, exclusive prefix sum of seq_lens */
+    uint64_t run_prefix_off[3];                /* uint64[R+1] per op: first run of request r */
+    uint64_t runs_off[3];                      /* kvx_run[num_runs[op]] per op */
+    uint64_t num_runs[3];                      /* op index: 0 pack, 1 unpack, 2 convert; 0 if op not planned */
+} kvx_plan_tables;
+
+/* Bytes of device workspace kvx_plan needs for these inputs.  `s`/`sb` describe
+ * the sender side, `d`/`db` the receiver side; either pair may be NULL (then
+ * only pack, or only unpack, can be planned).  Validates sizes only. */
+kvx_status kvx_plan_workspace_bytes(const kvx_pool_desc *s, const kvx_batch_desc *sb,
+                                    const kvx_pool_desc *d, const kvx_batch_desc *db,
+                                    size_t *out_bytes);
+
+/* Builds the copy plan for layers [layer_begin, layer_end) -- the offsets and
+ * lengths that section 3.6 says follow from layer index, prompt length, hidden
+ * size and precision, and the "meta" exchanged before a transfer.
+ *
+ * Host part: validates everything (see kvx_status), computes T_r and the
+ * payload size.  Device part, enqueued on `stream`: one copy of lengths and
+ * block tables into the workspace, a wavefront prefix-scan kernel over the
+ * variable lengths, and a kernel that writes the kvx_run records.  The plan
+ * may be used on `stream` right away, and on other streams after `stream` has
+ * been synchronised with them.
+ *
+ * With a sender side the plan serves kvx_pack, with a receiver side
+ * kvx_unpack, with both also kvx_convert.  Both sides must then agree in
+ * num_requests, seq_lens, num_kv_heads, head_dim and elem_bytes, and both must
+ * have at least layer_end layers.  Sender pages may repeat (shared prefixes);
+ * a receiver page used by two live logical pages is KVX_ERR_BLOCK_TABLE.
+ *
+ * dev_workspace [device] must be 256-byte aligned and at least
+ * kvx_plan_workspace_bytes large; it must stay alive and unmodified while the
+ * plan is in use.  dev_workspace == NULL with workspace_bytes == 0 builds a
+ * host-only plan: no HIP call is made; totals and segments can be queried but
+ * pack / unpack / convert return KVX_ERR_INVALID_ARG.
+ *
+ * KVX_ERR_UNSUPPORTED: page_tokens*row >= 2^32, or more than 2^32-1 tiles. */
+kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb,
+                    const kvx_pool_desc *d, const kvx_batch_desc *db,
+                    uint32_t layer_begin, uint32_t layer_end,
+                    void *dev_workspace, size_t workspace_bytes, void *stream,
+                    kvx_plan_t **out_plan);
+
+void kvx_plan_destroy(kvx_plan_t *plan);
+
+/* Size of the contiguous buffer: (l1-l0) * 2 * num_kv_heads * head_dim *
+ * elem_bytes * sum(seq_lens), the KV size formula of section 2.1. */
+kvx_status kvx_plan_total_bytes(const kvx_plan_t *plan, uint64_t *payload_bytes);
+
+/* Offset and length, inside the buffer, of the K and V rows of one layer of one
+ * request (section 3.6: per-layer or whole-model transfer by different offsets
+ * and lengths).  `layer` is absolute and must lie in the plan's range. */
+kvx_status kvx_plan_segment(const kvx_plan_t *plan, uint32_t request, uint32_t layer,
+                            uint64_t *offset, uint64_t *length);
+
+/* Offset and length of a whole request (all layers of the plan's range). */
+kvx_status kvx_plan_request_segment(const kvx_plan_t *plan, uint32_t request,
+                                    uint64_t *offset, uint64_t *length);
+
+kvx_status kvx_plan_get_tables(const kvx_plan_t *plan, kvx_plan_tables *out);
+kvx_status kvx_plan_set_launch(kvx_plan_t *plan, const kvx_launch_cfg *cfg);
+kvx_status kvx_plan_get_launch(const kvx_plan_t *plan, kvx_launch_cfg *out);
+
+/* Sender: src_pool [device] -> buf [device].  Writes exactly the first
+ * kvx_plan_total_bytes bytes of buf; buf_bytes smaller than that is
+ * KVX_ERR_CAPACITY.  One kernel launch. */
+kvx_status kvx_pack(const kvx_plan_t *plan, const void *src_pool, void *buf, uint64_t buf_bytes,
+                    void *stream);
+
+/* Receiver (RecvScatter): buf [device] -> dst_pool [device].  Writes only the
+ * live slots of the pages the receiver's block tables list.  One kernel launch. */
+kvx_status kvx_unpack(const kvx_plan_t *plan, const void *buf, uint64_t buf_bytes, void *dst_pool,
+                      void *stream);
+
+/* Pool to pool in one launch, equal to kvx_unpack after kvx_pack byte for byte,
+ * with independent page sizes and layouts on the two sides.  The pools must not
+ * overlap. */
+kvx_status kvx_convert(const kvx_plan_t *plan, const void *src_pool, void *dst_pool, void *stream);
+
+const char *kvx_status_string(kvx_status st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVX_H */

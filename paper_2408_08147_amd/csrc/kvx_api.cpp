@@ -1,0 +1,564 @@
+// Host side of libkvx: argument validation, plan construction, launches.
+// The operations and their layout conventions are stated in include/kvx.h
+// (paper section 3.6, "Block-free D2D KVCache Transfer").
+#include <algorithm>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <numeric>
+#include <vector>
+
+#include "kvx_internal.h"
+
+using namespace kvx;
+
+namespace {
+
+constexpr uint64_t kAlign = 256;
+inline uint64_t align_up(uint64_t x, uint64_t a = kAlign) { return (x + a - 1) / a * a; }
+
+struct Geometry {
+    bool present = false;
+    kvx_pool_desc desc{};
+    uint64_t row = 0;
+    uint64_t sl = 0, sk = 0, sp = 0, st = 0; // resolved byte strides
+    uint32_t quantum = 0;                    // tokens contiguous inside a page
+    uint64_t used_pages = 0;                 // sum over requests of ceil(n/P)
+};
+
+// Pinned staging blocks are costly to create, so destroyed plans hand theirs
+// back to a small free list instead of freeing them.  A block carries an event
+// recorded behind the H2D copy that reads it; it is handed out again only once
+// that event has completed, so a plan destroyed with work still queued never
+// has its staged tables overwritten before they were copied.
+struct PinnedBlock {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+    hipEvent_t copied = nullptr;
+};
+std::mutex g_pinned_mu;
+std::vector<PinnedBlock> g_pinned_free;
+
+hipError_t pinned_acquire(size_t bytes, PinnedBlock *out) {
+    {
+        std::lock_guard<std::mutex> lk(g_pinned_mu);
+        for (size_t i = 0; i < g_pinned_free.size(); ++i) {
+            if (g_pinned_free[i].bytes >= bytes && g_pinned_free[i].bytes <= 4 * bytes + 4096 &&
+                hipEventQuery(g_pinned_free[i].copied) == hipSuccess) {
+                *out = g_pinned_free[i];
+                g_pinned_free.erase(g_pinned_free.begin() + i);
+                return hipSuccess;
+            }
+        }
+    }
+    size_t cap = std::max<size_t>(align_up(bytes, 4096), 4096);
+    void *p = nullptr;
+    hipError_t e = hipHostMalloc(&p, cap, hipHostMallocDefault);
+    if (e != hipSuccess) return e;
+    hipEvent_t ev = nullptr;
+    e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        (void)hipHostFree(p);
+        return e;
+    }
+    out->ptr = p;
+    out->bytes = cap;
+    out->copied = ev;
+    return hipSuccess;
+}
+
+void pinned_release(PinnedBlock b) {
+    if (!b.ptr) return;
+    std::lock_guard<std::mutex> lk(g_pinned_mu);
+    // Never unmapped while a copy may still read it: the list simply grows.
+    g_pinned_free.push_back(b);
+}
+
+kvx_status resolve_pool(const kvx_pool_desc *d, Geometry *g) {
+    if (!d->num_layers || !d->num_kv_heads || !d->head_dim || !d->elem_bytes || !d->page_tokens ||
+        !d->num_pages || d->reserved)
+        return KVX_ERR_INVALID_ARG;
+    g->present = true;
+    g->desc = *d;
+    const uint64_t row = (uint64_t)d->num_kv_heads * d->head_dim * d->elem_bytes;
+    if (row % 16) return KVX_ERR_ALIGNMENT;
+    if (row * d->page_tokens >= (1ull << 32)) return KVX_ERR_UNSUPPORTED;
+    g->row = row;
+    const bool any = d->stride_layer || d->stride_kv || d->stride_page || d->stride_token;
+    if (any) {
+        if (!d->stride_layer || !d->stride_kv || !d->stride_page || !d->stride_token)
+            return KVX_ERR_INVALID_ARG;
+        if ((d->stride_layer | d->stride_kv | d->stride_page | d->stride_token) % 16)
+            return KVX_ERR_ALIGNMENT;
+        if (d->stride_token < row) return KVX_ERR_INVALID_ARG;
+        g->sl = d->stride_layer;
+        g->sk = d->stride_kv;
+        g->sp = d->stride_page;
+        g->st = d->stride_token;
+    } else if (d->layout == KVX_LAYOUT_LAYER_MAJOR) {
+        g->st = row;
+        g->sp = row * d->page_tokens;
+        g->sk = g->sp * d->num_pages;
+        g->sl = 2 * g->sk;
+    } else if (d->layout == KVX_LAYOUT_PAGE_MAJOR) {
+        g->st = row;
+        g->sk = row * d->page_tokens;
+        g->sl = 2 * g->sk;
+        g->sp = g->sl * d->num_layers;
+    } else {
+        return KVX_ERR_INVALID_ARG;
+    }
+    g->quantum = (g->st == row) ? d->page_tokens : 1u;
+    return KVX_OK;
+}
+
+kvx_status check_batch_shape(const kvx_batch_desc *b) {
+    if (b->reserved) return KVX_ERR_INVALID_ARG;
+    if (!b->block_offsets) return KVX_ERR_INVALID_ARG;
+    if (b->num_requests && !b->seq_lens) return KVX_ERR_INVALID_ARG;
+    if (b->block_offsets[0] != 0) return KVX_ERR_BLOCK_TABLE;
+    for (uint32_t r = 0; r < b->num_requests; ++r)
+        if (b->block_offsets[r + 1] < b->block_offsets[r]) return KVX_ERR_BLOCK_TABLE;
+    if (b->block_offsets[b->num_requests] && !b->block_ids) return KVX_ERR_INVALID_ARG;
+    return KVX_OK;
+}
+
+// Checks one side's block tables against its pool and gathers the ids that
+// are actually used (the first ceil(n/P) of each request) into `compact`.
+kvx_status check_tables(const Geometry &g, const kvx_batch_desc *b, bool receiver,
+                        std::vector<uint32_t> *compact, uint64_t *used_pages) {
+    const uint32_t P = g.desc.page_tokens;
+    uint64_t used = 0;
+    for (uint32_t r = 0; r < b->num_requests; ++r) {
+        const uint64_t need = ((uint64_t)b->seq_lens[r] + P - 1) / P;
+        if (need > b->block_offsets[r + 1] - b->block_offsets[r]) return KVX_ERR_BLOCK_TABLE;
+        used += need;
+    }
+    if (compact) compact->reserve(used);
+    std::vector<uint64_t> seen;
+    if (receiver) seen.assign(((uint64_t)g.desc.num_pages + 63) / 64, 0);
+    for (uint32_t r = 0; r < b->num_requests; ++r) {
+        const uint64_t need = ((uint64_t)b->seq_lens[r] + P - 1) / P;
+        const uint32_t *ids = b->block_ids + b->block_offsets[r];
+        for (uint64_t j = 0; j < need; ++j) {
+            const uint32_t id = ids[j];
+            if (id >= g.desc.num_pages) return KVX_ERR_BLOCK_TABLE;
+            if (receiver) {
+                uint64_t &w = seen[id >> 6];
+                const uint64_t bit = 1ull << (id & 63);
+                if (w & bit) return KVX_ERR_BLOCK_TABLE;
+                w |= bit;
+            }
+            if (compact) compact->push_back(id);
+        }
+    }
+    *used_pages = used;
+    return KVX_OK;
+}
+
+uint64_t ceil_div_q(uint64_t x, uint64_t q) {
+    if (q == 0) return x ? 1 : 0;
+    return (x + q - 1) / q;
+}
+
+uint64_t lcm_q(uint32_t a, uint32_t b) {
+    if (a == 0 || b == 0) return 0;
+    return (uint64_t)a / std::gcd(a, b) * b;
+}
+
+struct OpShape {
+    bool planned = false;
+    uint32_t qa = 0, qb = 0;
+    uint64_t lcm = 0;
+    uint64_t num_runs = 0;
+    uint32_t max_run_bytes = 0;
+};
+
+// Sizes shared by kvx_plan_workspace_bytes and kvx_plan.
+struct Sizing {
+    uint32_t R = 0;
+    OpShape ops[NUM_OPS];
+    uint64_t off_lens = 0, off_ids_s = 0, off_ids_d = 0, staging_bytes = 0;
+    uint64_t off_prefix[kNumScans] = {};
+    uint64_t off_runs[NUM_OPS] = {};
+    uint64_t total_bytes = 0;
+};
+
+void shape_ops(const Geometry &s, const Geometry &d, const uint32_t *seq_lens, uint32_t R,
+               OpShape ops[NUM_OPS]) {
+    if (s.present) {
+        ops[OP_PACK].planned = true;
+        ops[OP_PACK].qa = s.quantum;
+        ops[OP_PACK].qb = 0;
+    }
+    if (d.present) {
+        ops[OP_UNPACK].planned = true;
+        ops[OP_UNPACK].qa = 0;
+        ops[OP_UNPACK].qb = d.quantum;
+    }
+    if (s.present && d.present) {
+        ops[OP_CONVERT].planned = true;
+        ops[OP_CONVERT].qa = s.quantum;
+        ops[OP_CONVERT].qb = d.quantum;
+    }
+    const uint64_t row = s.present ? s.row : d.row;
+    for (int op = 0; op < (int)NUM_OPS; ++op) {
+        OpShape &o = ops[op];
+        if (!o.planned) continue;
+        o.lcm = lcm_q(o.qa, o.qb);
+        uint64_t q = o.qa && o.qb ? std::min(o.qa, o.qb) : std::max(o.qa, o.qb);
+        o.max_run_bytes = (uint32_t)(q * row);
+        uint64_t runs = 0;
+        for (uint32_t r = 0; r < R; ++r) {
+            const uint64_t n = seq_lens[r];
+            if (n) runs += ceil_div_q(n, o.qa) + ceil_div_q(n, o.qb) - ceil_div_q(n, o.lcm);
+        }
+        o.num_runs = runs;
+    }
+}
+
+void layout_workspace(Sizing *z, uint64_t used_s, uint64_t used_d) {
+    uint64_t off = 0;
+    z->off_lens = off;
+    off = align_up(off + 4ull * z->R);
+    z->off_ids_s = off;
+    off = align_up(off + 4ull * used_s);
+    z->off_ids_d = off;
+    off = align_up(off + 4ull * used_d);
+    z->staging_bytes = off;
+    for (int k = 0; k < kNumScans; ++k) {
+        z->off_prefix[k] = off;
+        off = align_up(off + 8ull * (z->R + 1ull));
+    }
+    for (int op = 0; op < (int)NUM_OPS; ++op) {
+        z->off_runs[op] = off;
+        off = align_up(off + sizeof(kvx_run) * z->ops[op].num_runs);
+    }
+    z->total_bytes = std::max<uint64_t>(off, kAlign);
+}
+
+kvx_status check_sides(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_pool_desc *d,
+                       const kvx_batch_desc *db, Geometry *gs, Geometry *gd) {
+    if ((!s) != (!sb) || (!d) != (!db) || (!s && !d)) return KVX_ERR_INVALID_ARG;
+    kvx_status st;
+    if (s) {
+        if ((st = resolve_pool(s, gs)) != KVX_OK) return st;
+        if ((st = check_batch_shape(sb)) != KVX_OK) return st;
+    }
+    if (d) {
+        if ((st = resolve_pool(d, gd)) != KVX_OK) return st;
+        if ((st = check_batch_shape(db)) != KVX_OK) return st;
+    }
+    if (s && d) {
+        if (s->num_kv_heads != d->num_kv_heads || s->head_dim != d->head_dim ||
+            s->elem_bytes != d->elem_bytes || sb->num_requests != db->num_requests)
+            return KVX_ERR_INVALID_ARG;
+        if (sb->num_requests && sb->seq_lens != db->seq_lens &&
+            std::memcmp(sb->seq_lens, db->seq_lens, 4ull * sb->num_requests) != 0)
+            return KVX_ERR_INVALID_ARG;
+    }
+    return KVX_OK;
+}
+
+} // namespace
+
+struct kvx_plan_s {
+    Geometry s, d;
+    uint32_t R = 0;
+    uint32_t l0 = 0, l1 = 0;
+    uint64_t row = 0;
+    uint64_t bpt = 0;
+    uint64_t total = 0;
+    std::vector<uint32_t> seq_lens;
+    std::vector<uint64_t> token_prefix; // T_r, host copy for segment queries
+    Sizing z;
+    char *ws = nullptr; // device workspace (caller's), nullptr for a host-only plan
+    PinnedBlock staging;
+    kvx_launch_cfg launch{};
+};
+
+namespace {
+void default_launch(kvx_launch_cfg *c) {
+    if (!c->unroll) c->unroll = 4;
+    if (!c->nontemporal) c->nontemporal = 2;
+    if (!c->order) c->order = 1;
+    if (!c->xcd_swizzle) c->xcd_swizzle = 1;
+    if (!c->max_workgroups) c->max_workgroups = 1u << 22;
+}
+} // namespace
+
+extern "C" {
+
+const char *kvx_status_string(kvx_status st) {
+    switch (st) {
+    case KVX_OK: return "ok";
+    case KVX_ERR_INVALID_ARG: return "invalid argument";
+    case KVX_ERR_ALIGNMENT: return "row, stride or pointer not a multiple of 16 bytes";
+    case KVX_ERR_BLOCK_TABLE: return "bad block table";
+    case KVX_ERR_CAPACITY: return "buffer or workspace too small";
+    case KVX_ERR_UNSUPPORTED: return "size not supported";
+    case KVX_ERR_DEVICE: return "HIP error";
+    }
+    return "unknown status";
+}
+
+kvx_status kvx_plan_workspace_bytes(const kvx_pool_desc *s, const kvx_batch_desc *sb,
+                                    const kvx_pool_desc *d, const kvx_batch_desc *db,
+                                    size_t *out_bytes) {
+    if (!out_bytes) return KVX_ERR_INVALID_ARG;
+    Geometry gs, gd;
+    kvx_status st = check_sides(s, sb, d, db, &gs, &gd);
+    if (st != KVX_OK) return st;
+    const kvx_batch_desc *b = sb ? sb : db;
+    uint64_t used_s = 0, used_d = 0;
+    if (s && (st = check_tables(gs, sb, false, nullptr, &used_s)) != KVX_OK) return st;
+    if (d && (st = check_tables(gd, db, false, nullptr, &used_d)) != KVX_OK) return st;
+    Sizing z;
+    z.R = b->num_requests;
+    shape_ops(gs, gd, b->seq_lens, z.R, z.ops);
+    layout_workspace(&z, used_s, used_d);
+    *out_bytes = (size_t)z.total_bytes;
+    return KVX_OK;
+}
+
+kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_pool_desc *d,
+                    const kvx_batch_desc *db, uint32_t layer_begin, uint32_t layer_end,
+                    void *dev_workspace, size_t workspace_bytes, void *stream,
+                    kvx_plan_t **out_plan) {
+    if (!out_plan) return KVX_ERR_INVALID_ARG;
+    *out_plan = nullptr;
+    kvx_plan_s *p = new (std::nothrow) kvx_plan_s;
+    if (!p) return KVX_ERR_INVALID_ARG;
+    kvx_status st = check_sides(s, sb, d, db, &p->s, &p->d);
+    if (st != KVX_OK) { delete p; return st; }
+    if (layer_begin > layer_end || (s && layer_end > s->num_layers) || (d && layer_end > d->num_layers)) {
+        delete p;
+        return KVX_ERR_INVALID_ARG;
+    }
+    if ((dev_workspace == nullptr) != (workspace_bytes == 0)) { delete p; return KVX_ERR_INVALID_ARG; }
+    if ((uintptr_t)dev_workspace % kAlign) { delete p; return KVX_ERR_ALIGNMENT; }
+
+    const kvx_batch_desc *b = sb ? sb : db;
+    const uint32_t R = b->num_requests;
+    std::vector<uint32_t> ids_s, ids_d;
+    if (s && (st = check_tables(p->s, sb, false, &ids_s, &p->s.used_pages)) != KVX_OK) { delete p; return st; }
+    if (d && (st = check_tables(p->d, db, true, &ids_d, &p->d.used_pages)) != KVX_OK) { delete p; return st; }
+
+    p->R = R;
+    p->l0 = layer_begin;
+    p->l1 = layer_end;
+    p->row = s ? p->s.row : p->d.row;
+    p->bpt = (uint64_t)(layer_end - layer_begin) * 2 * p->row;
+    p->seq_lens.assign(b->seq_lens, b->seq_lens + R);
+    p->token_prefix.resize((size_t)R + 1);
+    p->token_prefix[0] = 0;
+    for (uint32_t r = 0; r < R; ++r) p->token_prefix[r + 1] = p->token_prefix[r] + p->seq_lens[r];
+    p->total = p->token_prefix[R] * p->bpt;
+
+    Sizing &z = p->z;
+    z.R = R;
+    shape_ops(p->s, p->d, p->seq_lens.data(), R, z.ops);
+    layout_workspace(&z, p->s.used_pages, p->d.used_pages);
+    default_launch(&p->launch);
+    const uint64_t num_lc = 2ull * (layer_end - layer_begin);
+    for (int op = 0; op < (int)NUM_OPS; ++op) {
+        // even the smallest tile (one 16-byte load per lane) must give a 32-bit tile count
+        const uint64_t tpr = (z.ops[op].max_run_bytes + tile_bytes(1) - 1) / tile_bytes(1);
+        if (z.ops[op].planned && z.ops[op].num_runs * tpr * num_lc >= (1ull << 32)) {
+            delete p;
+            return KVX_ERR_UNSUPPORTED;
+        }
+    }
+
+    if (dev_workspace) {
+        if (workspace_bytes < z.total_bytes) { delete p; return KVX_ERR_CAPACITY; }
+        p->ws = static_cast<char *>(dev_workspace);
+        hipStream_t hs = static_cast<hipStream_t>(stream);
+        if (pinned_acquire((size_t)std::max<uint64_t>(z.staging_bytes, 16), &p->staging) != hipSuccess) {
+            delete p;
+            return KVX_ERR_DEVICE;
+        }
+        char *h = static_cast<char *>(p->staging.ptr);
+        if (R) std::memcpy(h + z.off_lens, p->seq_lens.data(), 4ull * R);
+        if (!ids_s.empty()) std::memcpy(h + z.off_ids_s, ids_s.data(), 4ull * ids_s.size());
+        if (!ids_d.empty()) std::memcpy(h + z.off_ids_d, ids_d.data(), 4ull * ids_d.size());
+        bool ok = true;
+        if (z.staging_bytes)
+            ok = hipMemcpyAsync(p->ws, h, z.staging_bytes, hipMemcpyHostToDevice, hs) == hipSuccess;
+        ok = ok && hipEventRecord(p->staging.copied, hs) == hipSuccess;
+
+        ScanParams sp{};
+        sp.seq_lens = reinterpret_cast<const uint32_t *>(p->ws + z.off_lens);
+        sp.num_requests = R;
+        sp.page_s = s ? s->page_tokens : 0;
+        sp.page_d = d ? d->page_tokens : 0;
+        FillParams fp{};
+        fp.seq_lens = sp.seq_lens;
+        fp.token_prefix = reinterpret_cast<const uint64_t *>(p->ws + z.off_prefix[SCAN_TOKENS]);
+        fp.num_requests = R;
+        fp.row = (uint32_t)p->row;
+        fp.bytes_per_token = p->bpt;
+        for (int k = 0; k < kNumScans; ++k) sp.prefix[k] = reinterpret_cast<uint64_t *>(p->ws + z.off_prefix[k]);
+        SideGeom src_side{}, dst_side{}, buf_side{};
+        if (s) {
+            src_side.ids = reinterpret_cast<const uint32_t *>(p->ws + z.off_ids_s);
+            src_side.page_prefix = sp.prefix[SCAN_PAGES_S];
+            src_side.stride_page = p->s.sp;
+            src_side.stride_token = p->s.st;
+            src_side.page_tokens = s->page_tokens;
+            src_side.quantum = p->s.quantum;
+        }
+        if (d) {
+            dst_side.ids = reinterpret_cast<const uint32_t *>(p->ws + z.off_ids_d);
+            dst_side.page_prefix = sp.prefix[SCAN_PAGES_D];
+            dst_side.stride_page = p->d.sp;
+            dst_side.stride_token = p->d.st;
+            dst_side.page_tokens = d->page_tokens;
+            dst_side.quantum = p->d.quantum;
+        }
+        fp.src[OP_PACK] = src_side;   fp.dst[OP_PACK] = buf_side;
+        fp.src[OP_UNPACK] = buf_side; fp.dst[OP_UNPACK] = dst_side;
+        fp.src[OP_CONVERT] = src_side; fp.dst[OP_CONVERT] = dst_side;
+        for (int op = 0; op < (int)NUM_OPS; ++op) {
+            sp.qa[op] = z.ops[op].qa;
+            sp.qb[op] = z.ops[op].qb;
+            sp.lcm[op] = z.ops[op].lcm;
+            sp.planned[op] = z.ops[op].planned;
+            fp.lcm[op] = z.ops[op].lcm;
+            fp.planned[op] = z.ops[op].planned;
+            fp.run_prefix[op] = sp.prefix[SCAN_RUNS0 + op];
+            fp.runs[op] = reinterpret_cast<kvx_run *>(p->ws + z.off_runs[op]);
+        }
+        ok = ok && launch_scan(sp, hs) == hipSuccess;
+        ok = ok && launch_fill(fp, hs) == hipSuccess;
+        if (!ok) {
+            pinned_release(p->staging);
+            delete p;
+            return KVX_ERR_DEVICE;
+        }
+    }
+    *out_plan = p;
+    return KVX_OK;
+}
+
+void kvx_plan_destroy(kvx_plan_t *plan) {
+    if (!plan) return;
+    // Work already enqueued with this plan keeps running: launches carry their
+    // arguments, and the staging block is recycled only after its copy is done.
+    pinned_release(plan->staging);
+    delete plan;
+}
+
+kvx_status kvx_plan_total_bytes(const kvx_plan_t *plan, uint64_t *payload_bytes) {
+    if (!plan || !payload_bytes) return KVX_ERR_INVALID_ARG;
+    *payload_bytes = plan->total;
+    return KVX_OK;
+}
+
+kvx_status kvx_plan_segment(const kvx_plan_t *plan, uint32_t request, uint32_t layer, uint64_t *offset,
+                            uint64_t *length) {
+    if (!plan || !offset || !length) return KVX_ERR_INVALID_ARG;
+    if (request >= plan->R || layer < plan->l0 || layer >= plan->l1) return KVX_ERR_INVALID_ARG;
+    const uint64_t n = plan->seq_lens[request];
+    *offset = plan->token_prefix[request] * plan->bpt + (uint64_t)(layer - plan->l0) * 2 * n * plan->row;
+    *length = 2 * n * plan->row;
+    return KVX_OK;
+}
+
+kvx_status kvx_plan_request_segment(const kvx_plan_t *plan, uint32_t request, uint64_t *offset,
+                                    uint64_t *length) {
+    if (!plan || !offset || !length || request >= plan->R) return KVX_ERR_INVALID_ARG;
+    *offset = plan->token_prefix[request] * plan->bpt;
+    *length = (uint64_t)plan->seq_lens[request] * plan->bpt;
+    return KVX_OK;
+}
+
+kvx_status kvx_plan_get_tables(const kvx_plan_t *plan, kvx_plan_tables *out) {
+    if (!plan || !out || !plan->ws) return KVX_ERR_INVALID_ARG;
+    out->token_prefix_off = plan->z.off_prefix[SCAN_TOKENS];
+    for (int op = 0; op < (int)NUM_OPS; ++op) {
+        out->run_prefix_off[op] = plan->z.off_prefix[SCAN_RUNS0 + op];
+        out->runs_off[op] = plan->z.off_runs[op];
+        out->num_runs[op] = plan->z.ops[op].planned ? plan->z.ops[op].num_runs : 0;
+    }
+    return KVX_OK;
+}
+
+kvx_status kvx_plan_set_launch(kvx_plan_t *plan, const kvx_launch_cfg *cfg) {
+    if (!plan || !cfg) return KVX_ERR_INVALID_ARG;
+    kvx_launch_cfg c = *cfg;
+    default_launch(&c);
+    if (c.unroll != 1 && c.unroll != 2 && c.unroll != 4 && c.unroll != 8) return KVX_ERR_INVALID_ARG;
+    if (c.nontemporal > 2 || c.order > 2 || c.xcd_swizzle > 2) return KVX_ERR_INVALID_ARG;
+    plan->launch = c;
+    return KVX_OK;
+}
+
+kvx_status kvx_plan_get_launch(const kvx_plan_t *plan, kvx_launch_cfg *out) {
+    if (!plan || !out) return KVX_ERR_INVALID_ARG;
+    *out = plan->launch;
+    return KVX_OK;
+}
+
+} // extern "C"
+
+namespace {
+
+kvx_status run_op(const kvx_plan_t *plan, Op op, const void *src, void *dst, void *stream) {
+    const OpShape &o = plan->z.ops[op];
+    if (!plan->ws || !o.planned) return KVX_ERR_INVALID_ARG;
+    if (plan->total == 0) return KVX_OK;
+    if (!src || !dst) return KVX_ERR_INVALID_ARG;
+    if (((uintptr_t)src | (uintptr_t)dst) % 16) return KVX_ERR_ALIGNMENT;
+    const kvx_launch_cfg &c = plan->launch;
+    CopyParams cp{};
+    cp.runs = reinterpret_cast<const kvx_run *>(plan->ws + plan->z.off_runs[op]);
+    cp.src = static_cast<const char *>(src);
+    cp.dst = static_cast<char *>(dst);
+    cp.src_is_buf = (op == OP_UNPACK);
+    cp.dst_is_buf = (op == OP_PACK);
+    cp.src_stride_layer = plan->s.sl;
+    cp.src_stride_kv = plan->s.sk;
+    cp.dst_stride_layer = plan->d.sl;
+    cp.dst_stride_kv = plan->d.sk;
+    cp.row = (uint32_t)plan->row;
+    cp.layer_begin = plan->l0;
+    cp.num_lc = 2 * (plan->l1 - plan->l0);
+    cp.num_runs = (uint32_t)o.num_runs;
+    const uint32_t tile = tile_bytes(c.unroll);
+    cp.tiles_per_run = (o.max_run_bytes + tile - 1) / tile;
+    cp.total_tiles = (uint32_t)((uint64_t)cp.num_lc * cp.num_runs * cp.tiles_per_run);
+    cp.order = c.order;
+    uint32_t grid = std::min(cp.total_tiles, c.max_workgroups);
+    if (c.xcd_swizzle == 2) {
+        grid = (grid + 7u) / 8u * 8u;
+        cp.swizzle_chunk = grid / 8u;
+    }
+    hipError_t e = launch_copy(cp, c.unroll, c.nontemporal == 2, grid, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? KVX_OK : KVX_ERR_DEVICE;
+}
+
+} // namespace
+
+extern "C" {
+
+kvx_status kvx_pack(const kvx_plan_t *plan, const void *src_pool, void *buf, uint64_t buf_bytes,
+                    void *stream) {
+    if (!plan) return KVX_ERR_INVALID_ARG;
+    if (buf_bytes < plan->total) return KVX_ERR_CAPACITY;
+    return run_op(plan, OP_PACK, src_pool, buf, stream);
+}
+
+kvx_status kvx_unpack(const kvx_plan_t *plan, const void *buf, uint64_t buf_bytes, void *dst_pool,
+                      void *stream) {
+    if (!plan) return KVX_ERR_INVALID_ARG;
+    if (buf_bytes < plan->total) return KVX_ERR_CAPACITY;
+    return run_op(plan, OP_UNPACK, buf, dst_pool, stream);
+}
+
+kvx_status kvx_convert(const kvx_plan_t *plan, const void *src_pool, void *dst_pool, void *stream) {
+    if (!plan) return KVX_ERR_INVALID_ARG;
+    return run_op(plan, OP_CONVERT, src_pool, dst_pool, stream);
+}
+
+} // extern "C"

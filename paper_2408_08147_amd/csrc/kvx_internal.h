@@ -1,0 +1,78 @@
+// Internal interface between the host side of libkvx (plan construction and
+// validation) and its HIP kernels.  Not installed; the public boundary is
+// include/kvx.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvx.h"
+
+namespace kvx {
+
+enum Op : uint32_t { OP_PACK = 0, OP_UNPACK = 1, OP_CONVERT = 2, NUM_OPS = 3 };
+
+// Number of prefix arrays the scan kernel produces, each uint64[R+1]:
+// tokens, sender pages, receiver pages, runs of pack / unpack / convert.
+constexpr int kNumScans = 6;
+enum Scan : int { SCAN_TOKENS = 0, SCAN_PAGES_S = 1, SCAN_PAGES_D = 2, SCAN_RUNS0 = 3 };
+
+// One side of a copy as the run-building kernel sees it.  quantum == 0 means
+// the contiguous buffer (no page boundary ever breaks a run).
+struct SideGeom {
+    const uint32_t *ids;         // compact block table: exactly ceil(n_r/page_tokens) ids per request
+    const uint64_t *page_prefix; // uint64[R+1], first id of request r in `ids`
+    uint64_t stride_page;
+    uint64_t stride_token;
+    uint32_t page_tokens;
+    uint32_t quantum;            // tokens that are contiguous: page_tokens, 1 (padded rows) or 0 (buffer)
+};
+
+struct ScanParams {
+    const uint32_t *seq_lens;
+    uint32_t num_requests;
+    uint32_t page_s, page_d;     // 0 = side absent
+    uint32_t qa[NUM_OPS], qb[NUM_OPS]; // contiguity quanta of source / destination per op (0 = buffer)
+    uint64_t lcm[NUM_OPS];       // lcm(qa,qb); 0 = infinite
+    uint32_t planned[NUM_OPS];
+    uint64_t *prefix[kNumScans]; // outputs
+};
+
+struct FillParams {
+    const uint32_t *seq_lens;
+    const uint64_t *token_prefix;
+    uint32_t num_requests;
+    uint32_t row;
+    uint64_t bytes_per_token;    // (l1-l0)*2*row
+    SideGeom src[NUM_OPS], dst[NUM_OPS];
+    uint64_t lcm[NUM_OPS];
+    uint32_t planned[NUM_OPS];
+    const uint64_t *run_prefix[NUM_OPS];
+    kvx_run *runs[NUM_OPS];
+};
+
+struct CopyParams {
+    const kvx_run *runs;
+    const char *src;
+    char *dst;
+    uint64_t src_stride_layer, src_stride_kv; // pool side only
+    uint64_t dst_stride_layer, dst_stride_kv;
+    uint32_t src_is_buf, dst_is_buf;
+    uint32_t row;
+    uint32_t layer_begin;
+    uint32_t num_lc;          // 2 * layers in range
+    uint32_t num_runs;
+    uint32_t tiles_per_run;
+    uint32_t total_tiles;     // num_lc * num_runs * tiles_per_run
+    uint32_t order;           // 1: (layer,kv) outermost   2: run outermost
+    uint32_t swizzle_chunk;   // 0 = off, else tiles per XCD (grid is a multiple of 8)
+};
+
+constexpr uint32_t kCopyThreads = 256;
+inline uint32_t tile_bytes(uint32_t unroll) { return kCopyThreads * 16u * unroll; }
+
+hipError_t launch_scan(const ScanParams &p, hipStream_t stream);
+hipError_t launch_fill(const FillParams &p, hipStream_t stream);
+hipError_t launch_copy(const CopyParams &p, uint32_t unroll, bool nontemporal, uint32_t grid,
+                       hipStream_t stream);
+
+} // namespace kvx

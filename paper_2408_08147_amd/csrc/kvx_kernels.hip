@@ -1,0 +1,254 @@
+// HIP kernels of libkvx for gfx950 (CDNA4, 64-wide wavefronts).
+//
+//   scan_kernel  exclusive prefix sums over the variable request lengths
+//                (tokens, pages per side, copy runs per operation), done with
+//                wavefront-level shuffles and one LDS hop across the waves of
+//                a single workgroup.  These are the offsets section 3.6 of the
+//                paper derives from prompt length, hidden size and precision.
+//   fill_kernel  writes the flat copy plan: one kvx_run per maximal span of
+//                tokens that is contiguous on both sides of an operation.
+//   copy_kernel  the pack / unpack / convert data mover: every workgroup takes
+//                tiles of (run, layer, K|V) and moves them with 16-byte loads
+//                and stores, all loads of a tile in flight before its first
+//                store.  No LDS: with token rows contiguous on both sides no
+//                byte changes its position inside a 16-byte unit.
+#include "kvx_internal.h"
+
+namespace kvx {
+
+using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint64_t ceil_div_q(uint64_t x, uint64_t q) {
+    // q == 0 stands for an infinite quantum: only x == 0 has no multiple below it.
+    if (q == 0) return x ? 1 : 0;
+    return (x + q - 1) / q;
+}
+
+// Number of maximal runs of n tokens cut at multiples of qa and of qb.
+__device__ __forceinline__ uint64_t count_runs(uint64_t n, uint32_t qa, uint32_t qb, uint64_t l) {
+    if (n == 0) return 0;
+    return ceil_div_q(n, qa) + ceil_div_q(n, qb) - ceil_div_q(n, l);
+}
+
+// ---------------------------------------------------------------------------
+// scan
+// ---------------------------------------------------------------------------
+constexpr int kScanThreads = 1024;
+constexpr int kScanWaves = kScanThreads / 64;
+
+__global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanParams p) {
+    __shared__ uint64_t wave_tot[kNumScans][kScanWaves];
+    __shared__ uint64_t carry[kNumScans];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = tid >> 6;
+    if (tid < kNumScans) carry[tid] = 0;
+    __syncthreads();
+
+    for (uint32_t base = 0; base < p.num_requests; base += kScanThreads) {
+        const uint32_t r = base + tid;
+        uint64_t v[kNumScans];
+#pragma unroll
+        for (int k = 0; k < kNumScans; ++k) v[k] = 0;
+        if (r < p.num_requests) {
+            const uint64_t n = p.seq_lens[r];
+            v[SCAN_TOKENS] = n;
+            v[SCAN_PAGES_S] = p.page_s ? (n + p.page_s - 1) / p.page_s : 0;
+            v[SCAN_PAGES_D] = p.page_d ? (n + p.page_d - 1) / p.page_d : 0;
+#pragma unroll
+            for (int op = 0; op < (int)NUM_OPS; ++op)
+                v[SCAN_RUNS0 + op] = p.planned[op] ? count_runs(n, p.qa[op], p.qb[op], p.lcm[op]) : 0;
+        }
+        uint64_t inc[kNumScans];
+#pragma unroll
+        for (int k = 0; k < kNumScans; ++k) {
+            uint64_t x = v[k];
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                uint64_t y = __shfl_up(x, d, 64);
+                if ((int)lane >= d) x += y;
+            }
+            inc[k] = x;
+            if (lane == 63) wave_tot[k][wave] = x;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kNumScans; ++k) {
+            uint64_t before = carry[k];
+            for (uint32_t w = 0; w < wave; ++w) before += wave_tot[k][w];
+            if (r < p.num_requests) p.prefix[k][r] = before + inc[k] - v[k];
+            inc[k] += before; // inclusive, global
+        }
+        __syncthreads();
+        if (tid == kScanThreads - 1) {
+#pragma unroll
+            for (int k = 0; k < kNumScans; ++k) carry[k] = inc[k];
+        }
+        __syncthreads();
+    }
+    if (tid < kNumScans) p.prefix[tid][p.num_requests] = carry[tid];
+}
+
+// ---------------------------------------------------------------------------
+// fill
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t side_offset(const SideGeom &g, uint32_t r, uint64_t x,
+                                                uint64_t buf_base, uint32_t row) {
+    if (g.quantum == 0) return buf_base + x * row;
+    const uint64_t logical = x / g.page_tokens;
+    const uint64_t slot = x % g.page_tokens;
+    const uint64_t page = g.ids[g.page_prefix[r] + logical];
+    return page * g.stride_page + slot * g.stride_token;
+}
+
+constexpr int kFillThreads = 256;
+
+// grid: x = request, y = operation
+__global__ __launch_bounds__(kFillThreads) void fill_kernel(FillParams p) {
+    const uint32_t op = blockIdx.y;
+    if (!p.planned[op]) return;
+    const SideGeom &a = p.src[op];
+    const SideGeom &b = p.dst[op];
+    const uint64_t l = p.lcm[op];
+    for (uint32_t r = blockIdx.x; r < p.num_requests; r += gridDim.x) {
+        const uint64_t n = p.seq_lens[r];
+        if (n == 0) continue;
+        const uint64_t ca = ceil_div_q(n, a.quantum);
+        const uint64_t cb = ceil_div_q(n, b.quantum);
+        const uint64_t buf_base = p.token_prefix[r] * p.bytes_per_token;
+        kvx_run *out = p.runs[op] + p.run_prefix[op][r];
+        for (uint64_t i = threadIdx.x; i < ca + cb; i += kFillThreads) {
+            uint64_t x;
+            if (i < ca) {
+                x = i * a.quantum; // quantum 0 -> ca == 1 -> x == 0
+            } else {
+                x = (i - ca) * b.quantum;
+                const bool also_a = a.quantum ? (x % a.quantum == 0) : (x == 0);
+                if (also_a) continue; // that boundary belongs to the other side's thread
+            }
+            const uint64_t rank = ceil_div_q(x, a.quantum) + ceil_div_q(x, b.quantum) - ceil_div_q(x, l);
+            uint64_t end = n;
+            if (a.quantum) end = min(end, (x / a.quantum + 1) * a.quantum);
+            if (b.quantum) end = min(end, (x / b.quantum + 1) * b.quantum);
+            kvx_run run;
+            run.src_off = side_offset(a, r, x, buf_base, p.row);
+            run.dst_off = side_offset(b, r, x, buf_base, p.row);
+            run.bytes = (uint32_t)((end - x) * p.row);
+            run.seq_len = (uint32_t)n;
+            run.request = r;
+            run.token = (uint32_t)x;
+            out[rank] = run;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// copy
+// ---------------------------------------------------------------------------
+template <bool NT>
+__device__ __forceinline__ u32x4 ld16(const char *p) {
+    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return *reinterpret_cast<const u32x4 *>(p);
+}
+template <bool NT>
+__device__ __forceinline__ void st16(char *p, u32x4 v) {
+    if (NT) __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
+    else *reinterpret_cast<u32x4 *>(p) = v;
+}
+
+template <int U, bool NT>
+__global__ __launch_bounds__(kCopyThreads) void copy_kernel(const kvx_run *__restrict__ runs,
+                                                            const char *__restrict__ src,
+                                                            char *__restrict__ dst, CopyParams p) {
+    constexpr uint32_t kStep = kCopyThreads * 16u; // bytes one load instruction of the workgroup covers
+    constexpr uint32_t kTile = kStep * U;
+    const uint32_t lane_off = threadIdx.x * 16u;
+
+    uint32_t first = blockIdx.x;
+    if (p.swizzle_chunk) first = (blockIdx.x & 7u) * p.swizzle_chunk + (blockIdx.x >> 3);
+
+    for (uint64_t v64 = first; v64 < p.total_tiles; v64 += gridDim.x) {
+        const uint32_t v = (uint32_t)v64;
+        uint32_t lc, e, s;
+        if (p.order == 2) {
+            s = v % p.tiles_per_run;
+            const uint32_t q = v / p.tiles_per_run;
+            lc = q % p.num_lc;
+            e = q / p.num_lc;
+        } else {
+            s = v % p.tiles_per_run;
+            const uint32_t q = v / p.tiles_per_run;
+            e = q % p.num_runs;
+            lc = q / p.num_runs;
+        }
+        const kvx_run run = runs[e];
+        const uint32_t base = s * kTile;
+        if (base >= run.bytes) continue;
+        const uint32_t rem = run.bytes - base;
+
+        const uint32_t layer = p.layer_begin + (lc >> 1);
+        const uint32_t kv = lc & 1u;
+        const uint64_t seg = (uint64_t)lc * run.seq_len * p.row; // (layer,kv) step inside a request's buffer
+        const uint64_t so = run.src_off + base +
+                            (p.src_is_buf ? seg : layer * p.src_stride_layer + kv * p.src_stride_kv);
+        const uint64_t dk = run.dst_off + base +
+                            (p.dst_is_buf ? seg : layer * p.dst_stride_layer + kv * p.dst_stride_kv);
+        const char *sp = src + so + lane_off;
+        char *dp = dst + dk + lane_off;
+
+        u32x4 r[U];
+        if (rem >= kTile) {
+#pragma unroll
+            for (int k = 0; k < U; ++k) r[k] = ld16<NT>(sp + k * kStep);
+#pragma unroll
+            for (int k = 0; k < U; ++k) st16<NT>(dp + k * kStep, r[k]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+                if (lane_off + k * kStep < rem) r[k] = ld16<NT>(sp + k * kStep);
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+                if (lane_off + k * kStep < rem) st16<NT>(dp + k * kStep, r[k]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+hipError_t launch_scan(const ScanParams &p, hipStream_t stream) {
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(kScanThreads), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill(const FillParams &p, hipStream_t stream) {
+    if (p.num_requests == 0) return hipSuccess;
+    const uint32_t gx = p.num_requests < 65535u ? p.num_requests : 65535u;
+    hipLaunchKernelGGL(fill_kernel, dim3(gx, NUM_OPS), dim3(kFillThreads), 0, stream, p);
+    return hipGetLastError();
+}
+
+template <int U>
+static hipError_t launch_copy_u(const CopyParams &p, bool nt, uint32_t grid, hipStream_t stream) {
+    if (nt)
+        hipLaunchKernelGGL((copy_kernel<U, true>), dim3(grid), dim3(kCopyThreads), 0, stream, p.runs, p.src,
+                           p.dst, p);
+    else
+        hipLaunchKernelGGL((copy_kernel<U, false>), dim3(grid), dim3(kCopyThreads), 0, stream, p.runs, p.src,
+                           p.dst, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy(const CopyParams &p, uint32_t unroll, bool nontemporal, uint32_t grid,
+                       hipStream_t stream) {
+    if (p.total_tiles == 0 || grid == 0) return hipSuccess;
+    switch (unroll) {
+    case 1: return launch_copy_u<1>(p, nontemporal, grid, stream);
+    case 2: return launch_copy_u<2>(p, nontemporal, grid, stream);
+    case 4: return launch_copy_u<4>(p, nontemporal, grid, stream);
+    case 8: return launch_copy_u<8>(p, nontemporal, grid, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+} // namespace kvx

@@ -1,0 +1,151 @@
+"""Shared plumbing of the GPU parity tests: put a case on the device, run the
+library through its C ABI, run the oracle on the same bytes, hand both back."""
+from __future__ import annotations
+
+import os
+from dataclasses import dataclass, field
+from typing import Optional, Tuple
+
+import numpy as np
+
+from oracle import kvxo
+from paper_2408_08147_amd import kvx
+
+ORACLE_THREADS = min(8, os.cpu_count() or 1)
+CANARY_POOL = 0xC3
+CANARY_BUF = 0x5A
+BUF_SLACK = 4096
+
+
+@dataclass
+class Side:
+    page_tokens: int
+    num_pages: int
+    layout: int = 0
+    strides: Tuple[int, int, int, int] = (0, 0, 0, 0)
+    span_bytes: int = 0          # allocation size when strides are explicit
+
+
+@dataclass
+class Case:
+    num_layers: int
+    num_kv_heads: int
+    head_dim: int
+    elem_bytes: int
+    seq_lens: np.ndarray
+    s: Side
+    d: Side
+    ids_s: np.ndarray
+    offs_s: np.ndarray
+    ids_d: np.ndarray
+    offs_d: np.ndarray
+
+    @property
+    def row(self):
+        return self.num_kv_heads * self.head_dim * self.elem_bytes
+
+    def pool_bytes(self, side: Side) -> int:
+        if any(side.strides):
+            return side.span_bytes
+        return self.num_layers * 2 * side.num_pages * side.page_tokens * self.row
+
+    def kvx_pool(self, side: Side):
+        return kvx.pool_desc(self.num_layers, self.num_kv_heads, self.head_dim, self.elem_bytes,
+                             side.page_tokens, side.num_pages, side.layout, side.strides)
+
+    def oracle_pool(self, side: Side):
+        return kvxo.Pool(self.num_layers, self.num_kv_heads, self.head_dim, self.elem_bytes,
+                         side.page_tokens, side.num_pages, side.layout, *side.strides)
+
+
+def tables(rng, seq_lens, P, num_pages, unique=True, extra=0):
+    need = [(int(n) + P - 1) // P for n in seq_lens]
+    if unique:
+        it = iter(rng.permutation(num_pages))
+        rows = [[int(next(it)) for _ in range(k + extra)] for k in need]
+    else:
+        rows = [[int(x) for x in rng.integers(0, num_pages, size=k + extra)] for k in need]
+    offs = np.zeros(len(seq_lens) + 1, dtype=np.uint64)
+    offs[1:] = np.cumsum([len(x) for x in rows])
+    return np.array([x for r in rows for x in r], dtype=np.uint32), offs
+
+
+def make_case(rng, L, H, D, e, lens, Ps, Pd, ls=0, ld=0, shared_src=False, extra=0, slack_pages=3):
+    lens = np.asarray(lens, dtype=np.uint32)
+    used_s = int(sum((int(n) + Ps - 1) // Ps + extra for n in lens))
+    used_d = int(sum((int(n) + Pd - 1) // Pd + extra for n in lens))
+    nps, npd = 2 * used_s + slack_pages, 2 * used_d + slack_pages
+    ids_s, offs_s = tables(rng, lens, Ps, nps, unique=not shared_src, extra=extra)
+    ids_d, offs_d = tables(rng, lens, Pd, npd, unique=True, extra=extra)
+    return Case(L, H, D, e, lens, Side(Ps, nps, ls), Side(Pd, npd, ld), ids_s, offs_s, ids_d, offs_d)
+
+
+@dataclass
+class Result:
+    total: int
+    buf: np.ndarray            # total + BUF_SLACK bytes
+    dst_unpack: np.ndarray
+    dst_convert: np.ndarray
+    extra: dict = field(default_factory=dict)
+
+
+def run_oracle(case: Case, src: np.ndarray, l0: int, l1: int) -> Result:
+    ps, pd = case.oracle_pool(case.s), case.oracle_pool(case.d)
+    bs = kvxo.Batch(case.seq_lens, case.ids_s, case.offs_s)
+    bd = kvxo.Batch(case.seq_lens, case.ids_d, case.offs_d)
+    total = kvxo.total_bytes(ps, bs, l0, l1)
+    buf = np.full(total + BUF_SLACK, CANARY_BUF, dtype=np.uint8)
+    kvxo.pack(ps, bs, l0, l1, src, buf, threads=ORACLE_THREADS)
+    du = np.full(case.pool_bytes(case.d), CANARY_POOL, dtype=np.uint8)
+    kvxo.unpack(pd, bd, l0, l1, buf, du, threads=ORACLE_THREADS)
+    dc = np.full(case.pool_bytes(case.d), CANARY_POOL, dtype=np.uint8)
+    kvxo.convert(ps, bs, pd, bd, l0, l1, src, dc, threads=ORACLE_THREADS)
+    return Result(total, buf, du, dc)
+
+
+def run_gpu(case: Case, src: np.ndarray, l0: int, l1: int, launch: Optional[dict] = None,
+            want_tables: bool = False) -> Result:
+    import torch
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream(device=dev)
+    sp, dp = case.kvx_pool(case.s), case.kvx_pool(case.d)
+    sb = kvx.BatchDesc(case.seq_lens, case.ids_s, case.offs_s)
+    db = kvx.BatchDesc(case.seq_lens, case.ids_d, case.offs_d)
+    ws_bytes = kvx.kvx_plan_workspace_bytes(sp, sb, dp, db)
+    with torch.cuda.stream(stream):
+        ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)
+        src_t = torch.from_numpy(src).to(dev, non_blocking=False)
+        plan = kvx.kvx_plan(sp, sb, dp, db, l0, l1, ws.data_ptr(), ws_bytes, stream.cuda_stream)
+        if launch:
+            kvx.kvx_plan_set_launch(plan, **launch)
+        total = kvx.kvx_plan_total_bytes(plan)
+        buf = torch.full((total + BUF_SLACK,), CANARY_BUF, dtype=torch.uint8, device=dev)
+        du = torch.full((case.pool_bytes(case.d),), CANARY_POOL, dtype=torch.uint8, device=dev)
+        dc = torch.full((case.pool_bytes(case.d),), CANARY_POOL, dtype=torch.uint8, device=dev)
+        kvx.kvx_pack(plan, src_t.data_ptr(), buf.data_ptr(), total, stream.cuda_stream)
+        kvx.kvx_unpack(plan, buf.data_ptr(), total, du.data_ptr(), stream.cuda_stream)
+        kvx.kvx_convert(plan, src_t.data_ptr(), dc.data_ptr(), stream.cuda_stream)
+    stream.synchronize()
+    res = Result(total, buf.cpu().numpy(), du.cpu().numpy(), dc.cpu().numpy())
+    assert np.array_equal(src_t.cpu().numpy(), src), "the source pool was modified"
+    if want_tables:
+        t = kvx.kvx_plan_get_tables(plan)
+        w = ws.cpu().numpy()
+        R = len(case.seq_lens)
+        res.extra["token_prefix"] = w[t.token_prefix_off:t.token_prefix_off + 8 * (R + 1)].view("<u8")
+        for op in range(3):
+            res.extra[f"run_prefix{op}"] = w[t.run_prefix_off[op]:t.run_prefix_off[op] + 8 * (R + 1)].view("<u8")
+            n = int(t.num_runs[op])
+            res.extra[f"runs{op}"] = w[t.runs_off[op]:t.runs_off[op] + 32 * n].view(kvx.RUN_DTYPE)
+    plan.destroy()
+    return res
+
+
+def assert_same(got: Result, want: Result, what: str = ""):
+    assert got.total == want.total, what
+    for name in ("buf", "dst_unpack", "dst_convert"):
+        a, b = getattr(got, name), getattr(want, name)
+        assert a.shape == b.shape, (what, name)
+        if not np.array_equal(a, b):
+            bad = np.flatnonzero(a != b)
+            raise AssertionError(f"{what} {name}: {bad.size} bytes differ, first at {bad[0]}")

@@ -1,0 +1,232 @@
+"""GPU parity: kvx_pack / kvx_unpack / kvx_convert through the C ABI against the
+CPU oracle, byte for byte (buffer incl. slack, destination pools incl. every
+byte that must stay untouched), at sizes the oracle finishes in seconds."""
+import numpy as np
+import pytest
+
+from paper_2408_08147_amd import kvx
+from paper_2408_08147_amd import workloads as W
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+LM, PM = 0, 1
+
+
+def check(case, seed, ranges=None, launch=None, kind="bytes"):
+    rng = np.random.default_rng(seed)
+    if kind == "bytes":
+        src = rng.integers(0, 256, size=case.pool_bytes(case.s), dtype=np.uint8)
+    else:
+        src = W.values_numpy(kind, case.pool_bytes(case.s), rng)
+    for l0, l1 in ranges or [(0, case.num_layers)]:
+        want = G.run_oracle(case, src, l0, l1)
+        got = G.run_gpu(case, src, l0, l1, launch=launch)
+        G.assert_same(got, want, f"layers [{l0},{l1})")
+
+
+# ------------------------------------------------------------------ edge cases
+EDGE_LENS = {
+    "empty_batch": [],
+    "all_zero": [0, 0, 0],
+    "single_token": [1],
+    "around_page": [15, 16, 17, 0, 31, 32, 33, 1],
+    "ragged_multi_tile": [1000, 3, 517, 128, 129, 2047],
+}
+
+
+@pytest.mark.parametrize("name", sorted(EDGE_LENS))
+@pytest.mark.parametrize("Ps,Pd,ls,ld", [(16, 16, LM, LM), (128, 16, LM, PM), (16, 128, PM, LM)])
+def test_edge_lengths(name, Ps, Pd, ls, ld):
+    rng = np.random.default_rng(sum(map(ord, name)) + Ps)
+    case = G.make_case(rng, 3, 2, 64, 2, EDGE_LENS[name], Ps, Pd, ls, ld)
+    check(case, 1, ranges=[(0, 3), (1, 2), (2, 2)])
+
+
+@pytest.mark.parametrize("Ps,Pd", [(5, 7), (7, 5), (24, 16), (1, 1), (1, 64), (64, 1), (3, 128)])
+@pytest.mark.parametrize("ls,ld", [(LM, LM), (PM, PM), (LM, PM)])
+def test_page_sizes_that_do_not_divide(Ps, Pd, ls, ld):
+    rng = np.random.default_rng(Ps * 1000 + Pd)
+    lens = [0, 1, 34, 35, 36, 211, 500, Ps, Pd, Ps * Pd + 1]
+    case = G.make_case(rng, 2, 1, 16, 1, lens, Ps, Pd, ls, ld)      # 16-byte rows: the smallest allowed
+    check(case, 2)
+
+
+def test_shared_source_pages_and_extra_ids():
+    rng = np.random.default_rng(5)
+    case = G.make_case(rng, 2, 2, 32, 2, [100, 7, 260, 33], 16, 8, LM, PM, shared_src=True, extra=2)
+    check(case, 3)
+
+
+def test_explicit_strides_padded_rows_and_pages():
+    """Caller-given strides: rows padded (no two tokens adjacent) on the sender,
+    pages padded on the receiver."""
+    rng = np.random.default_rng(6)
+    L, H, D, e, Ps, Pd = 2, 2, 32, 2, 8, 4
+    row = H * D * e
+    lens = np.array([9, 0, 40, 8, 17], dtype=np.uint32)
+    nps, npd = 24, 48
+    st_tok_s = row + 32
+    st_page_s = Ps * st_tok_s + 64
+    st_kv_s = nps * st_page_s
+    st_layer_s = 2 * st_kv_s + 256
+    s = G.Side(Ps, nps, 0, (st_layer_s, st_kv_s, st_page_s, st_tok_s), L * st_layer_s)
+    st_page_d = Pd * row + 48
+    st_kv_d = npd * st_page_d
+    st_layer_d = 2 * st_kv_d
+    d = G.Side(Pd, npd, 0, (st_layer_d, st_kv_d, st_page_d, row), L * st_layer_d)
+    ids_s, offs_s = G.tables(rng, lens, Ps, nps)
+    ids_d, offs_d = G.tables(rng, lens, Pd, npd)
+    case = G.Case(L, H, D, e, lens, s, d, ids_s, offs_s, ids_d, offs_d)
+    check(case, 4, ranges=[(0, 2), (1, 2)])
+
+
+# ------------------------------------------------------------------ launch geometry does not matter
+@pytest.mark.parametrize("launch", [
+    dict(unroll=1), dict(unroll=2, nontemporal=1), dict(unroll=8, order=2),
+    dict(unroll=4, xcd_swizzle=2), dict(unroll=8, xcd_swizzle=2, order=2, max_workgroups=24),
+    dict(unroll=2, max_workgroups=7), dict(unroll=4, nontemporal=1, max_workgroups=1),
+])
+def test_results_do_not_depend_on_launch_config(launch):
+    rng = np.random.default_rng(7)
+    case = G.make_case(rng, 3, 4, 64, 2, [700, 1, 129, 64, 300, 0, 33], 32, 16, LM, PM)
+    check(case, 5, launch=launch)
+
+
+# ------------------------------------------------------------------ the five workloads, oracle-sized
+def workload_case(idx, **scaled):
+    w = W.CONFIGS[idx].scaled(**scaled) if scaled else W.CONFIGS[idx]
+    b = W.draw_batch(w)
+    return w, G.Case(w.num_layers, w.num_kv_heads, w.head_dim, w.elem_bytes, b.seq_lens,
+                     G.Side(w.page_s, b.num_pages_s, w.layout_s), G.Side(w.page_d, b.num_pages_d, w.layout_d),
+                     b.ids_s, b.offs_s, b.ids_d, b.offs_d)
+
+
+def test_workload_1_tiny_full():
+    w, case = workload_case(1)
+    check(case, w.seed, kind=w.value_kind, ranges=[(0, 2), (1, 2)])
+
+
+def test_workload_2_scaled():
+    w, case = workload_case(2, num_layers=2, num_requests=4)
+    check(case, w.seed, kind=w.value_kind)
+
+
+def test_workload_3_scaled():
+    w, case = workload_case(3, num_layers=4, num_requests=24)
+    check(case, w.seed, kind=w.value_kind, ranges=[(0, 4), (3, 4)])
+
+
+def test_workload_4_scaled():
+    w, case = workload_case(4, num_layers=2, num_requests=8, len_hi=6000)
+    check(case, w.seed, kind=w.value_kind)
+
+
+def test_workload_5_scaled():
+    w, case = workload_case(5, num_layers=2, num_requests=256)
+    check(case, w.seed, kind=w.value_kind)
+
+
+# ------------------------------------------------------------------ the device-built plan itself
+@pytest.mark.parametrize("Ps,Pd", [(16, 16), (128, 16), (5, 7)])
+def test_device_plan_tables(Ps, Pd):
+    """The prefix scans and run records the kernels wrote: T_r is the exclusive
+    sum of lengths, and per operation the runs of a request tile its tokens
+    exactly once, in order, each run inside one page on both sides."""
+    rng = np.random.default_rng(Ps + Pd)
+    lens = rng.integers(0, 900, size=1500).astype(np.uint32)      # more requests than one scan pass holds
+    lens[::97] = 0
+    case = G.make_case(rng, 2, 1, 16, 1, lens, Ps, Pd, LM, PM)
+    src = np.zeros(case.pool_bytes(case.s), dtype=np.uint8)
+    res = G.run_gpu(case, src, 0, 2, want_tables=True)
+    T = np.concatenate([[0], np.cumsum(lens.astype(np.uint64))])
+    assert np.array_equal(res.extra["token_prefix"], T)
+    row, bpt = case.row, 2 * 2 * case.row
+    for op, (qa, qb) in enumerate([(Ps, None), (None, Pd), (Ps, Pd)]):
+        runs, pre = res.extra[f"runs{op}"], res.extra[f"run_prefix{op}"]
+        assert pre[0] == 0 and pre[-1] == len(runs)
+        assert np.all(np.diff(pre.astype(np.int64)) >= 0)
+        req = np.repeat(np.arange(len(lens)), np.diff(pre.astype(np.int64)))
+        assert np.array_equal(runs["request"], req)
+        assert np.array_equal(runs["seq_len"], lens[req])
+        tok, ntok = runs["token"].astype(np.int64), runs["bytes"].astype(np.int64) // row
+        assert np.all(runs["bytes"] % row == 0) and np.all(ntok > 0)
+        first = np.zeros(len(runs), dtype=bool)
+        first[pre[:-1][np.diff(pre.astype(np.int64)) > 0]] = True
+        assert np.all(tok[first] == 0)
+        nxt = tok + ntok
+        same_req = req[1:] == req[:-1]
+        assert np.all(tok[1:][same_req] == nxt[:-1][same_req])                 # contiguous inside a request
+        last = np.ones(len(runs), dtype=bool)
+        last[:-1] = ~same_req
+        assert np.array_equal(nxt[last], lens[req[last]].astype(np.int64))     # and they end at n_r
+        for q in (qa, qb):
+            if q:
+                assert np.all(tok // q == (nxt - 1) // q)                      # never crosses a page
+        buf_off = T[req].astype(np.int64) * bpt + tok * row
+        if qa is None:
+            assert np.array_equal(runs["src_off"].astype(np.int64), buf_off)
+        if qb is None:
+            assert np.array_equal(runs["dst_off"].astype(np.int64), buf_off)
+
+
+def test_plan_reuse_and_immediate_destroy():
+    """A plan can be used many times, and destroyed right after enqueueing."""
+    import torch
+    rng = np.random.default_rng(9)
+    case = G.make_case(rng, 2, 2, 64, 2, [300, 45, 1000], 16, 16)
+    src = rng.integers(0, 256, size=case.pool_bytes(case.s), dtype=np.uint8)
+    want = G.run_oracle(case, src, 0, 2)
+    dev = torch.device("cuda:0")
+    st = torch.cuda.Stream(device=dev)
+    sp, dp = case.kvx_pool(case.s), case.kvx_pool(case.d)
+    sb = kvx.BatchDesc(case.seq_lens, case.ids_s, case.offs_s)
+    db = kvx.BatchDesc(case.seq_lens, case.ids_d, case.offs_d)
+    nws = kvx.kvx_plan_workspace_bytes(sp, sb, dp, db)
+    with torch.cuda.stream(st):
+        src_t = torch.from_numpy(src).to(dev)
+        outs = []
+        for it in range(6):
+            ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+            plan = kvx.kvx_plan(sp, sb, dp, db, 0, 2, ws.data_ptr(), nws, st.cuda_stream)
+            buf = torch.full((want.total + G.BUF_SLACK,), G.CANARY_BUF, dtype=torch.uint8, device=dev)
+            dst = torch.full((case.pool_bytes(case.d),), G.CANARY_POOL, dtype=torch.uint8, device=dev)
+            for _ in range(2):
+                kvx.kvx_pack(plan, src_t.data_ptr(), buf.data_ptr(), want.total, st.cuda_stream)
+                kvx.kvx_unpack(plan, buf.data_ptr(), want.total, dst.data_ptr(), st.cuda_stream)
+            plan.destroy()
+            outs.append((ws, buf, dst))
+    st.synchronize()
+    for ws, buf, dst in outs:
+        assert np.array_equal(buf.cpu().numpy(), want.buf)
+        assert np.array_equal(dst.cpu().numpy(), want.dst_unpack)
+
+
+def test_runtime_argument_errors():
+    import torch
+    rng = np.random.default_rng(10)
+    case = G.make_case(rng, 1, 1, 64, 2, [40], 16, 16)
+    dev = torch.device("cuda:0")
+    sp = case.kvx_pool(case.s)
+    sb = kvx.BatchDesc(case.seq_lens, case.ids_s, case.offs_s)
+    nws = kvx.kvx_plan_workspace_bytes(sp, sb, None, None)
+    ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+    with pytest.raises(kvx.KvxError) as e:
+        kvx.kvx_plan(sp, sb, None, None, 0, 1, ws.data_ptr(), nws - 256)
+    assert e.value.status == kvx.ERR_CAPACITY
+    plan = kvx.kvx_plan(sp, sb, None, None, 0, 1, ws.data_ptr(), nws)
+    total = kvx.kvx_plan_total_bytes(plan)
+    pool = torch.zeros(case.pool_bytes(case.s), dtype=torch.uint8, device=dev)
+    buf = torch.zeros(total + 64, dtype=torch.uint8, device=dev)
+    for fn, args, status in [
+        (kvx.kvx_pack, (plan, pool.data_ptr(), buf.data_ptr(), total - 1), kvx.ERR_CAPACITY),
+        (kvx.kvx_pack, (plan, pool.data_ptr(), buf.data_ptr() + 8, total), kvx.ERR_ALIGNMENT),
+        (kvx.kvx_pack, (plan, 0, buf.data_ptr(), total), kvx.ERR_INVALID_ARG),
+        (kvx.kvx_unpack, (plan, buf.data_ptr(), total, pool.data_ptr()), kvx.ERR_INVALID_ARG),   # no receiver side
+        (kvx.kvx_convert, (plan, pool.data_ptr(), pool.data_ptr()), kvx.ERR_INVALID_ARG),
+    ]:
+        with pytest.raises(kvx.KvxError) as e:
+            fn(*args)
+        assert e.value.status == status
+    torch.cuda.synchronize()
+    plan.destroy()

@@ -1,0 +1,165 @@
+"""CPU-only checks of libkvx: the library loads and exports the whole boundary,
+and the host side of kvx_plan (validation, sizes, segments) behaves as
+include/kvx.h states.  No kernel is launched: plans are host-only."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import kvxo
+from paper_2408_08147_amd import kvx
+from paper_2408_08147_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    import ctypes
+    hdr = open(os.path.join(ROOT, "include", "kvx.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(kvx_[a-z_]+)\s*\(", hdr))
+    assert declared == set(kvx.EXPORTS), declared ^ set(kvx.EXPORTS)
+    lib = ctypes.CDLL(kvx.lib_path())
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings():
+    seen = {kvx.status_string(i) for i in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+
+
+def _simple(n=(100, 33), P=16, NP=64):
+    need = [(x + P - 1) // P for x in n]
+    ids = np.arange(sum(need), dtype=np.uint32)
+    offs = np.concatenate([[0], np.cumsum(need)]).astype(np.uint64)
+    return kvx.pool_desc(2, 8, 128, 2, P, NP), kvx.BatchDesc(n, ids, offs)
+
+
+def expect(status, fn, *a, **k):
+    with pytest.raises(kvx.KvxError) as e:
+        fn(*a, **k)
+    assert e.value.status == status, e.value
+
+
+def test_argument_errors():
+    s, b = _simple()
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, None, None, None, None, 0, 1)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, s, None, None, None, 0, 1)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, s, b, None, None, 1, 0)          # range reversed
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, s, b, None, None, 0, 3)          # beyond num_layers
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, s, b, None, None, 0, 2, 0, 4096) # size without pointer
+    expect(kvx.ERR_ALIGNMENT, kvx.kvx_plan, s, b, None, None, 0, 2, 128, 1 << 20)
+    zero = kvx.pool_desc(2, 8, 128, 2, 0, 64)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, zero, b, None, None, 0, 2)
+    odd = kvx.pool_desc(2, 1, 4, 2, 16, 64)                                    # row = 8 bytes
+    expect(kvx.ERR_ALIGNMENT, kvx.kvx_plan, odd, b, None, None, 0, 2)
+    badlayout = kvx.pool_desc(2, 8, 128, 2, 16, 64, layout=7)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, badlayout, b, None, None, 0, 2)
+    part = kvx.pool_desc(2, 8, 128, 2, 16, 64, strides=(1 << 20, 0, 0, 0))
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, part, b, None, None, 0, 2)
+    mis = kvx.pool_desc(2, 8, 128, 2, 16, 64, strides=(1 << 20, 1 << 19, 32776, 2048))
+    expect(kvx.ERR_ALIGNMENT, kvx.kvx_plan, mis, b, None, None, 0, 2)
+    short = kvx.pool_desc(2, 8, 128, 2, 16, 64, strides=(1 << 22, 1 << 21, 1 << 15, 1024))
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, short, b, None, None, 0, 2)      # stride_token < row
+    huge = kvx.pool_desc(1, 64, 256, 4, 1 << 16, 2)                            # page_tokens*row = 2^32
+    expect(kvx.ERR_UNSUPPORTED, kvx.kvx_plan, huge, kvx.BatchDesc([1], [0], [0, 1]), None, None, 0, 1)
+
+
+def test_sides_must_agree():
+    s, b = _simple()
+    d_heads = kvx.pool_desc(2, 4, 128, 2, 16, 64)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, s, b, d_heads, b, 0, 2)
+    d_elem = kvx.pool_desc(2, 8, 128, 1, 16, 64)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, s, b, d_elem, b, 0, 2)
+    _, b_other = _simple(n=(100, 34))
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, s, b, s, b_other, 0, 2)
+    _, b_three = _simple(n=(100, 33, 1))
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, s, b, s, b_three, 0, 2)
+    d_fewer_layers = kvx.pool_desc(1, 8, 128, 2, 16, 64)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, s, b, d_fewer_layers, b, 0, 2)
+    kvx.kvx_plan(s, b, d_fewer_layers, b, 0, 1).destroy()
+
+
+def test_block_table_errors():
+    s = kvx.pool_desc(2, 8, 128, 2, 16, 64)
+    ok = kvx.BatchDesc([100, 33], np.arange(10), [0, 7, 10])
+    kvx.kvx_plan(s, ok, s, ok, 0, 2).destroy()
+    too_short = kvx.BatchDesc([100, 33], np.arange(9), [0, 6, 9])
+    expect(kvx.ERR_BLOCK_TABLE, kvx.kvx_plan, s, too_short, None, None, 0, 2)
+    out_of_pool = kvx.BatchDesc([100, 33], [0, 1, 2, 3, 4, 5, 64, 7, 8, 9], [0, 7, 10])
+    expect(kvx.ERR_BLOCK_TABLE, kvx.kvx_plan, s, out_of_pool, None, None, 0, 2)
+    descending = kvx.BatchDesc([100, 33], np.arange(10), [0, 7, 5])
+    expect(kvx.ERR_BLOCK_TABLE, kvx.kvx_plan, s, descending, None, None, 0, 2)
+    nonzero_start = kvx.BatchDesc([100, 33], np.arange(12), [1, 8, 11])
+    expect(kvx.ERR_BLOCK_TABLE, kvx.kvx_plan, s, nonzero_start, None, None, 0, 2)
+    # a page twice: fine for a sender (shared prefix), an error for a receiver
+    dup = kvx.BatchDesc([100, 33], [0, 1, 2, 3, 4, 5, 6, 0, 1, 9], [0, 7, 10])
+    kvx.kvx_plan(s, dup, None, None, 0, 2).destroy()
+    kvx.kvx_plan(s, dup, s, ok, 0, 2).destroy()
+    expect(kvx.ERR_BLOCK_TABLE, kvx.kvx_plan, None, None, s, dup, 0, 2)
+    expect(kvx.ERR_BLOCK_TABLE, kvx.kvx_plan, s, ok, s, dup, 0, 2)
+    # ids beyond ceil(n/P) are ignored: they may repeat or leave the pool
+    extra = kvx.BatchDesc([100, 33], [0, 1, 2, 3, 4, 5, 6, 6, 999, 7, 8, 9, 7], [0, 9, 13])
+    kvx.kvx_plan(None, None, s, extra, 0, 2).destroy()
+    # zero-length requests need no pages
+    empty = kvx.BatchDesc([0, 16, 0], [3], [0, 0, 1, 1])
+    p = kvx.kvx_plan(s, empty, s, empty, 0, 2)
+    assert kvx.kvx_plan_total_bytes(p) == 16 * 2 * 2 * 2048
+    assert kvx.kvx_plan_request_segment(p, 0) == (0, 0)
+    assert kvx.kvx_plan_request_segment(p, 2) == (16 * 8192, 0)
+    none = kvx.BatchDesc([], [], [0])
+    p0 = kvx.kvx_plan(s, none, None, None, 0, 2)
+    assert kvx.kvx_plan_total_bytes(p0) == 0
+
+
+def test_host_only_plan_cannot_launch():
+    s, b = _simple()
+    p = kvx.kvx_plan(s, b, s, b, 0, 2)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_pack, p, 4096, 8192, 1 << 40)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_unpack, p, 4096, 1 << 40, 8192)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_convert, p, 4096, 8192)
+    expect(kvx.ERR_CAPACITY, kvx.kvx_pack, p, 4096, 8192, 10)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan_get_tables, p)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan_segment, p, 2, 0)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan_segment, p, 0, 2)
+
+
+def test_launch_config_round_trip():
+    s, b = _simple()
+    p = kvx.kvx_plan(s, b, None, None, 0, 2)
+    d = kvx.kvx_plan_get_launch(p)
+    assert d.unroll in (1, 2, 4, 8) and d.nontemporal in (1, 2) and d.order in (1, 2)
+    kvx.kvx_plan_set_launch(p, unroll=8, nontemporal=1, order=2, xcd_swizzle=2, max_workgroups=4096)
+    g = kvx.kvx_plan_get_launch(p)
+    assert (g.unroll, g.nontemporal, g.order, g.xcd_swizzle, g.max_workgroups) == (8, 1, 2, 2, 4096)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan_set_launch, p, unroll=3)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan_set_launch, p, order=5)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_totals_and_segments_match_oracle_on_the_five_workloads(idx):
+    """Host arithmetic of the library against the oracle's, at the full sizes
+    of the five synthetic workloads (64-bit offsets included)."""
+    w = W.CONFIGS[idx]
+    bt = W.draw_batch(w)
+    s = kvx.pool_desc(w.num_layers, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_s, bt.num_pages_s, w.layout_s)
+    d = kvx.pool_desc(w.num_layers, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_d, bt.num_pages_d, w.layout_d)
+    sb = kvx.BatchDesc(bt.seq_lens, bt.ids_s, bt.offs_s)
+    db = kvx.BatchDesc(bt.seq_lens, bt.ids_d, bt.offs_d)
+    op = kvxo.Pool(w.num_layers, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_s, bt.num_pages_s, w.layout_s)
+    ob = kvxo.Batch(bt.seq_lens, bt.ids_s, bt.offs_s)
+    rng = np.random.default_rng(idx)
+    for l0, l1 in [(0, w.num_layers), (1, 2), (w.num_layers - 1, w.num_layers)]:
+        p = kvx.kvx_plan(s, sb, d, db, l0, l1)
+        assert kvx.kvx_plan_total_bytes(p) == kvxo.total_bytes(op, ob, l0, l1)
+        for r in rng.integers(0, w.num_requests, size=8):
+            r = int(r)
+            for l in {l0, l1 - 1, int(rng.integers(l0, l1))}:
+                assert kvx.kvx_plan_segment(p, r, l) == kvxo.segment(op, ob, l0, l1, r, l)
+            off0, _ = kvxo.segment(op, ob, l0, l1, r, l0)
+            offn, lenn = kvxo.segment(op, ob, l0, l1, r, l1 - 1)
+            assert kvx.kvx_plan_request_segment(p, r) == (off0, offn + lenn - off0)
+        p.destroy()
+    assert kvx.kvx_plan_workspace_bytes(s, sb, d, db) % 256 == 0
