@@ -113,7 +113,8 @@ def cpu_baseline(setup: Setup, target_bytes: float = 1.5e9):
         out[label] = dict(pack_s=t1 - t0, unpack_s=t2 - t1, gbps=2 * total / (t2 - t0) / 1e9)
     # bonus parity at full shape: the GPU's result for these layers, through its own full-range plan
     plan = setup.plan()
-    setup.dst.fill_(0xC3)
+    with setup.torch.cuda.stream(setup.stream):
+        setup.dst.fill_(0xC3)
     setup.pack(plan)
     setup.unpack(plan)
     setup.stream.synchronize()

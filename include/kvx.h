@@ -102,7 +102,8 @@ typedef struct {
     uint32_t order;         /* 1 = (layer,kv) outermost, 2 = copy run outermost */
     uint32_t xcd_swizzle;   /* 1 = off, 2 = give each of the 8 XCDs a contiguous range of tiles */
     uint32_t max_workgroups;/* cap on the grid; tiles beyond it are taken in a grid-stride loop */
-    uint32_t reserved[3];
+    uint32_t threads;       /* lanes per workgroup: 64, 128, 256, 512 or 1024; a tile is threads*16*unroll bytes */
+    uint32_t reserved[2];
 } kvx_launch_cfg;
 
 typedef struct kvx_plan_s kvx_plan_t;
@@ -200,6 +201,16 @@ kvx_status kvx_unpack(const kvx_plan_t *plan, const void *buf, uint64_t buf_byte
  * with independent page sizes and layouts on the two sides.  The pools must not
  * overlap. */
 kvx_status kvx_convert(const kvx_plan_t *plan, const void *src_pool, void *dst_pool, void *stream);
+
+/* Yardstick, not part of the transfer: a plain contiguous device-to-device copy
+ * of `bytes` bytes (a multiple of 16; both pointers [device], 16-byte aligned,
+ * not overlapping) made of the same 16-byte loads and stores as the data
+ * mover, with `unroll`, `nontemporal` and `max_workgroups` taken from `cfg`
+ * (NULL = defaults).  It shows what fraction of
+ * the HBM peak a copy reaches on this device at all, and calibrates hardware
+ * byte counters against a transfer of known size. */
+kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const kvx_launch_cfg *cfg,
+                              void *stream);
 
 const char *kvx_status_string(kvx_status st);
 

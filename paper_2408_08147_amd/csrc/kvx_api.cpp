@@ -279,11 +279,12 @@ struct kvx_plan_s {
 
 namespace {
 void default_launch(kvx_launch_cfg *c) {
-    if (!c->unroll) c->unroll = 4;
+    if (!c->unroll) c->unroll = 1;
     if (!c->nontemporal) c->nontemporal = 2;
     if (!c->order) c->order = 1;
-    if (!c->xcd_swizzle) c->xcd_swizzle = 1;
-    if (!c->max_workgroups) c->max_workgroups = 1u << 22;
+    if (!c->xcd_swizzle) c->xcd_swizzle = 2;
+    if (!c->max_workgroups) c->max_workgroups = 1u << 24;
+    if (!c->threads) c->threads = 256;
 }
 } // namespace
 
@@ -363,7 +364,7 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
     const uint64_t num_lc = 2ull * (layer_end - layer_begin);
     for (int op = 0; op < (int)NUM_OPS; ++op) {
         // even the smallest tile (one 16-byte load per lane) must give a 32-bit tile count
-        const uint64_t tpr = (z.ops[op].max_run_bytes + tile_bytes(1) - 1) / tile_bytes(1);
+        const uint64_t tpr = (z.ops[op].max_run_bytes + tile_bytes(64, 1) - 1) / tile_bytes(64, 1);
         if (z.ops[op].planned && z.ops[op].num_runs * tpr * num_lc >= (1ull << 32)) {
             delete p;
             return KVX_ERR_UNSUPPORTED;
@@ -488,7 +489,7 @@ kvx_status kvx_plan_set_launch(kvx_plan_t *plan, const kvx_launch_cfg *cfg) {
     if (!plan || !cfg) return KVX_ERR_INVALID_ARG;
     kvx_launch_cfg c = *cfg;
     default_launch(&c);
-    if (c.unroll != 1 && c.unroll != 2 && c.unroll != 4 && c.unroll != 8) return KVX_ERR_INVALID_ARG;
+    if (!valid_unroll(c.unroll) || !valid_threads(c.threads)) return KVX_ERR_INVALID_ARG;
     if (c.nontemporal > 2 || c.order > 2 || c.xcd_swizzle > 2) return KVX_ERR_INVALID_ARG;
     plan->launch = c;
     return KVX_OK;
@@ -525,16 +526,19 @@ kvx_status run_op(const kvx_plan_t *plan, Op op, const void *src, void *dst, voi
     cp.layer_begin = plan->l0;
     cp.num_lc = 2 * (plan->l1 - plan->l0);
     cp.num_runs = (uint32_t)o.num_runs;
-    const uint32_t tile = tile_bytes(c.unroll);
+    const uint32_t tile = tile_bytes(c.threads, c.unroll);
     cp.tiles_per_run = (o.max_run_bytes + tile - 1) / tile;
     cp.total_tiles = (uint32_t)((uint64_t)cp.num_lc * cp.num_runs * cp.tiles_per_run);
     cp.order = c.order;
-    uint32_t grid = std::min(cp.total_tiles, c.max_workgroups);
+    // keep grid * threads below 2^31 work-items; the kernel's grid-stride loop takes the rest
+    const uint32_t grid_cap = std::min<uint32_t>(c.max_workgroups, (1u << 31) / c.threads - 8u);
+    uint32_t grid = std::min(cp.total_tiles, grid_cap);
     if (c.xcd_swizzle == 2) {
         grid = (grid + 7u) / 8u * 8u;
         cp.swizzle_chunk = grid / 8u;
     }
-    hipError_t e = launch_copy(cp, c.unroll, c.nontemporal == 2, grid, static_cast<hipStream_t>(stream));
+    hipError_t e = launch_copy(cp, c.threads, c.unroll, c.nontemporal == 2, grid,
+                               static_cast<hipStream_t>(stream));
     return e == hipSuccess ? KVX_OK : KVX_ERR_DEVICE;
 }
 
@@ -559,6 +563,20 @@ kvx_status kvx_unpack(const kvx_plan_t *plan, const void *buf, uint64_t buf_byte
 kvx_status kvx_convert(const kvx_plan_t *plan, const void *src_pool, void *dst_pool, void *stream) {
     if (!plan) return KVX_ERR_INVALID_ARG;
     return run_op(plan, OP_CONVERT, src_pool, dst_pool, stream);
+}
+
+kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const kvx_launch_cfg *cfg,
+                              void *stream) {
+    if (!dst || !src) return KVX_ERR_INVALID_ARG;
+    if ((((uintptr_t)dst | (uintptr_t)src) % 16) || bytes % 16) return KVX_ERR_ALIGNMENT;
+    kvx_launch_cfg c{};
+    if (cfg) c = *cfg;
+    default_launch(&c);
+    if (!valid_unroll(c.unroll) || !valid_threads(c.threads)) return KVX_ERR_INVALID_ARG;
+    hipError_t e = launch_plain_copy(static_cast<char *>(dst), static_cast<const char *>(src), bytes, c.threads,
+                                     c.unroll,
+                                     c.nontemporal == 2, c.max_workgroups, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? KVX_OK : KVX_ERR_DEVICE;
 }
 
 } // extern "C"

@@ -67,12 +67,16 @@ struct CopyParams {
     uint32_t swizzle_chunk;   // 0 = off, else tiles per XCD (grid is a multiple of 8)
 };
 
-constexpr uint32_t kCopyThreads = 256;
-inline uint32_t tile_bytes(uint32_t unroll) { return kCopyThreads * 16u * unroll; }
+inline uint32_t tile_bytes(uint32_t threads, uint32_t unroll) { return threads * 16u * unroll; }
+inline bool valid_threads(uint32_t t) { return t == 64 || t == 128 || t == 256 || t == 512 || t == 1024; }
+inline bool valid_unroll(uint32_t u) { return u == 1 || u == 2 || u == 4 || u == 8; }
 
 hipError_t launch_scan(const ScanParams &p, hipStream_t stream);
 hipError_t launch_fill(const FillParams &p, hipStream_t stream);
-hipError_t launch_copy(const CopyParams &p, uint32_t unroll, bool nontemporal, uint32_t grid,
+hipError_t launch_copy(const CopyParams &p, uint32_t threads, uint32_t unroll, bool nontemporal, uint32_t grid,
                        hipStream_t stream);
+
+hipError_t launch_plain_copy(char *dst, const char *src, uint64_t bytes, uint32_t threads, uint32_t unroll,
+                             bool nontemporal, uint32_t max_wg, hipStream_t stream);
 
 } // namespace kvx

@@ -12,6 +12,8 @@
 //                and stores, all loads of a tile in flight before its first
 //                store.  No LDS: with token rows contiguous on both sides no
 //                byte changes its position inside a 16-byte unit.
+#include <algorithm>
+
 #include "kvx_internal.h"
 
 namespace kvx {
@@ -156,11 +158,10 @@ __device__ __forceinline__ void st16(char *p, u32x4 v) {
     else *reinterpret_cast<u32x4 *>(p) = v;
 }
 
-template <int U, bool NT>
-__global__ __launch_bounds__(kCopyThreads) void copy_kernel(const kvx_run *__restrict__ runs,
-                                                            const char *__restrict__ src,
-                                                            char *__restrict__ dst, CopyParams p) {
-    constexpr uint32_t kStep = kCopyThreads * 16u; // bytes one load instruction of the workgroup covers
+template <int T, int U, bool NT>
+__global__ __launch_bounds__(T) void copy_kernel(const kvx_run *__restrict__ runs, const char *__restrict__ src,
+                                                 char *__restrict__ dst, CopyParams p) {
+    constexpr uint32_t kStep = T * 16u; // bytes one load instruction of the workgroup covers
     constexpr uint32_t kTile = kStep * U;
     const uint32_t lane_off = threadIdx.x * 16u;
 
@@ -169,15 +170,13 @@ __global__ __launch_bounds__(kCopyThreads) void copy_kernel(const kvx_run *__res
 
     for (uint64_t v64 = first; v64 < p.total_tiles; v64 += gridDim.x) {
         const uint32_t v = (uint32_t)v64;
-        uint32_t lc, e, s;
+        uint32_t lc, e;
+        const uint32_t s = v % p.tiles_per_run;
+        const uint32_t q = v / p.tiles_per_run;
         if (p.order == 2) {
-            s = v % p.tiles_per_run;
-            const uint32_t q = v / p.tiles_per_run;
             lc = q % p.num_lc;
             e = q / p.num_lc;
         } else {
-            s = v % p.tiles_per_run;
-            const uint32_t q = v / p.tiles_per_run;
             e = q % p.num_runs;
             lc = q / p.num_runs;
         }
@@ -213,6 +212,34 @@ __global__ __launch_bounds__(kCopyThreads) void copy_kernel(const kvx_run *__res
     }
 }
 
+// Plain contiguous copy with the data mover's access shape: the yardstick.
+template <int T, int U, bool NT>
+__global__ __launch_bounds__(T) void plain_copy_kernel(const char *__restrict__ src, char *__restrict__ dst,
+                                                       uint64_t bytes) {
+    constexpr uint32_t kStep = T * 16u;
+    constexpr uint64_t kTile = (uint64_t)kStep * U;
+    const uint32_t lane_off = threadIdx.x * 16u;
+    for (uint64_t base = (uint64_t)blockIdx.x * kTile; base < bytes; base += (uint64_t)gridDim.x * kTile) {
+        const uint64_t rem = bytes - base;
+        const char *sp = src + base + lane_off;
+        char *dp = dst + base + lane_off;
+        u32x4 r[U];
+        if (rem >= kTile) {
+#pragma unroll
+            for (int k = 0; k < U; ++k) r[k] = ld16<NT>(sp + k * kStep);
+#pragma unroll
+            for (int k = 0; k < U; ++k) st16<NT>(dp + k * kStep, r[k]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+                if (lane_off + k * kStep < rem) r[k] = ld16<NT>(sp + k * kStep);
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+                if (lane_off + k * kStep < rem) st16<NT>(dp + k * kStep, r[k]);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
@@ -228,25 +255,74 @@ hipError_t launch_fill(const FillParams &p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int U>
-static hipError_t launch_copy_u(const CopyParams &p, bool nt, uint32_t grid, hipStream_t stream) {
-    if (nt)
-        hipLaunchKernelGGL((copy_kernel<U, true>), dim3(grid), dim3(kCopyThreads), 0, stream, p.runs, p.src,
-                           p.dst, p);
-    else
-        hipLaunchKernelGGL((copy_kernel<U, false>), dim3(grid), dim3(kCopyThreads), 0, stream, p.runs, p.src,
-                           p.dst, p);
+namespace {
+
+// Dispatch of the runtime (threads, unroll, nontemporal) triple to a template instance.
+template <int T, int U>
+hipError_t copy_tu(const CopyParams &p, bool nt, uint32_t grid, hipStream_t stream) {
+    if (nt) hipLaunchKernelGGL((copy_kernel<T, U, true>), dim3(grid), dim3(T), 0, stream, p.runs, p.src, p.dst, p);
+    else hipLaunchKernelGGL((copy_kernel<T, U, false>), dim3(grid), dim3(T), 0, stream, p.runs, p.src, p.dst, p);
     return hipGetLastError();
 }
 
-hipError_t launch_copy(const CopyParams &p, uint32_t unroll, bool nontemporal, uint32_t grid,
+template <int T>
+hipError_t copy_t(const CopyParams &p, uint32_t unroll, bool nt, uint32_t grid, hipStream_t stream) {
+    switch (unroll) {
+    case 1: return copy_tu<T, 1>(p, nt, grid, stream);
+    case 2: return copy_tu<T, 2>(p, nt, grid, stream);
+    case 4: return copy_tu<T, 4>(p, nt, grid, stream);
+    case 8: return copy_tu<T, 8>(p, nt, grid, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+template <int T, int U>
+hipError_t plain_tu(char *dst, const char *src, uint64_t bytes, bool nt, uint32_t max_wg, hipStream_t stream) {
+    const uint64_t tile = (uint64_t)T * 16u * U;
+    const uint64_t tiles = (bytes + tile - 1) / tile;
+    const uint64_t cap = std::min<uint64_t>(max_wg, (1u << 31) / T);
+    const uint32_t grid = (uint32_t)(tiles < cap ? tiles : cap);
+    if (nt) hipLaunchKernelGGL((plain_copy_kernel<T, U, true>), dim3(grid), dim3(T), 0, stream, src, dst, bytes);
+    else hipLaunchKernelGGL((plain_copy_kernel<T, U, false>), dim3(grid), dim3(T), 0, stream, src, dst, bytes);
+    return hipGetLastError();
+}
+
+template <int T>
+hipError_t plain_t(char *dst, const char *src, uint64_t bytes, uint32_t unroll, bool nt, uint32_t max_wg,
+                   hipStream_t stream) {
+    switch (unroll) {
+    case 1: return plain_tu<T, 1>(dst, src, bytes, nt, max_wg, stream);
+    case 2: return plain_tu<T, 2>(dst, src, bytes, nt, max_wg, stream);
+    case 4: return plain_tu<T, 4>(dst, src, bytes, nt, max_wg, stream);
+    case 8: return plain_tu<T, 8>(dst, src, bytes, nt, max_wg, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+} // namespace
+
+hipError_t launch_copy(const CopyParams &p, uint32_t threads, uint32_t unroll, bool nontemporal, uint32_t grid,
                        hipStream_t stream) {
     if (p.total_tiles == 0 || grid == 0) return hipSuccess;
-    switch (unroll) {
-    case 1: return launch_copy_u<1>(p, nontemporal, grid, stream);
-    case 2: return launch_copy_u<2>(p, nontemporal, grid, stream);
-    case 4: return launch_copy_u<4>(p, nontemporal, grid, stream);
-    case 8: return launch_copy_u<8>(p, nontemporal, grid, stream);
+    switch (threads) {
+    case 64: return copy_t<64>(p, unroll, nontemporal, grid, stream);
+    case 128: return copy_t<128>(p, unroll, nontemporal, grid, stream);
+    case 256: return copy_t<256>(p, unroll, nontemporal, grid, stream);
+    case 512: return copy_t<512>(p, unroll, nontemporal, grid, stream);
+    case 1024: return copy_t<1024>(p, unroll, nontemporal, grid, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_plain_copy(char *dst, const char *src, uint64_t bytes, uint32_t threads, uint32_t unroll,
+                             bool nontemporal, uint32_t max_wg, hipStream_t stream) {
+    if (bytes == 0) return hipSuccess;
+    switch (threads) {
+    case 64: return plain_t<64>(dst, src, bytes, unroll, nontemporal, max_wg, stream);
+    case 128: return plain_t<128>(dst, src, bytes, unroll, nontemporal, max_wg, stream);
+    case 256: return plain_t<256>(dst, src, bytes, unroll, nontemporal, max_wg, stream);
+    case 512: return plain_t<512>(dst, src, bytes, unroll, nontemporal, max_wg, stream);
+    case 1024: return plain_t<1024>(dst, src, bytes, unroll, nontemporal, max_wg, stream);
     default: return hipErrorInvalidValue;
     }
 }

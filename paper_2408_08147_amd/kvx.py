@@ -22,7 +22,8 @@ OP_PACK, OP_UNPACK, OP_CONVERT = 0, 1, 2
 EXPORTS = (
     "kvx_plan_workspace_bytes", "kvx_plan", "kvx_plan_destroy", "kvx_plan_total_bytes",
     "kvx_plan_segment", "kvx_plan_request_segment", "kvx_plan_get_tables", "kvx_plan_set_launch",
-    "kvx_plan_get_launch", "kvx_pack", "kvx_unpack", "kvx_convert", "kvx_status_string",
+    "kvx_plan_get_launch", "kvx_pack", "kvx_unpack", "kvx_convert", "kvx_copy_yardstick",
+    "kvx_status_string",
 )
 
 
@@ -56,7 +57,7 @@ class _BatchDesc(C.Structure):
 class LaunchCfg(C.Structure):
     _fields_ = [("unroll", C.c_uint32), ("nontemporal", C.c_uint32), ("order", C.c_uint32),
                 ("xcd_swizzle", C.c_uint32), ("max_workgroups", C.c_uint32),
-                ("reserved", C.c_uint32 * 3)]
+                ("threads", C.c_uint32), ("reserved", C.c_uint32 * 2)]
 
 
 class PlanTables(C.Structure):
@@ -120,6 +121,7 @@ def load():
     lib.kvx_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
     lib.kvx_unpack.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
     lib.kvx_convert.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.kvx_copy_yardstick.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(LaunchCfg), C.c_void_p]
     for name in EXPORTS:
         if name not in ("kvx_status_string", "kvx_plan_destroy"):
             getattr(lib, name).restype = C.c_int
@@ -209,8 +211,8 @@ def kvx_plan_get_tables(plan: Plan) -> PlanTables:
 
 
 def kvx_plan_set_launch(plan: Plan, unroll: int = 0, nontemporal: int = 0, order: int = 0,
-                        xcd_swizzle: int = 0, max_workgroups: int = 0) -> None:
-    cfg = LaunchCfg(unroll, nontemporal, order, xcd_swizzle, max_workgroups)
+                        xcd_swizzle: int = 0, max_workgroups: int = 0, threads: int = 0) -> None:
+    cfg = LaunchCfg(unroll, nontemporal, order, xcd_swizzle, max_workgroups, threads)
     _check(load().kvx_plan_set_launch(plan.handle, C.byref(cfg)), "kvx_plan_set_launch")
 
 
@@ -233,6 +235,13 @@ def kvx_unpack(plan: Plan, buf: int, buf_bytes: int, dst_pool: int, stream: int 
 def kvx_convert(plan: Plan, src_pool: int, dst_pool: int, stream: int = 0) -> None:
     _check(load().kvx_convert(plan.handle, C.c_void_p(src_pool or None), C.c_void_p(dst_pool or None),
                               C.c_void_p(stream or None)), "kvx_convert")
+
+
+def kvx_copy_yardstick(dst: int, src: int, nbytes: int, stream: int = 0, unroll: int = 0,
+                       nontemporal: int = 0, max_workgroups: int = 0, threads: int = 0) -> None:
+    cfg = LaunchCfg(unroll, nontemporal, 0, 0, max_workgroups, threads)
+    _check(load().kvx_copy_yardstick(C.c_void_p(dst or None), C.c_void_p(src or None), nbytes, C.byref(cfg),
+                                     C.c_void_p(stream or None)), "kvx_copy_yardstick")
 
 
 def pool_desc(num_layers: int, num_kv_heads: int, head_dim: int, elem_bytes: int, page_tokens: int,

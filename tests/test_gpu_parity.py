@@ -86,6 +86,8 @@ def test_explicit_strides_padded_rows_and_pages():
     dict(unroll=1), dict(unroll=2, nontemporal=1), dict(unroll=8, order=2),
     dict(unroll=4, xcd_swizzle=2), dict(unroll=8, xcd_swizzle=2, order=2, max_workgroups=24),
     dict(unroll=2, max_workgroups=7), dict(unroll=4, nontemporal=1, max_workgroups=1),
+    dict(threads=64), dict(threads=128, unroll=2, xcd_swizzle=1), dict(threads=512, unroll=4, order=2),
+    dict(threads=1024, unroll=8), dict(threads=1024, unroll=1, max_workgroups=16),
 ])
 def test_results_do_not_depend_on_launch_config(launch):
     rng = np.random.default_rng(7)
