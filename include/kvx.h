@@ -99,7 +99,8 @@ typedef struct {
 typedef struct {
     uint32_t unroll;        /* 16-byte loads in flight per lane before the first store: 1,2,4,8 */
     uint32_t nontemporal;   /* 1 = off, 2 = non-temporal loads and stores */
-    uint32_t order;         /* 1 = (layer,kv) outermost, 2 = copy run outermost */
+    uint32_t order;         /* 0 = chosen per operation from the receiver's layout, 1 = (layer,kv) outermost,
+                               2 = copy run (for convert: group of runs) outermost */
     uint32_t xcd_swizzle;   /* 1 = off, 2 = give each of the 8 XCDs a contiguous range of tiles */
     uint32_t max_workgroups;/* cap on the grid; tiles beyond it are taken in a grid-stride loop */
     uint32_t threads;       /* lanes per workgroup: 64, 128, 256, 512 or 1024; a tile is threads*16*unroll bytes */
@@ -110,7 +111,9 @@ typedef struct kvx_plan_s kvx_plan_t;
 
 /* One record of the flat copy plan in the device workspace: a maximal span of
  * tokens of one request that is contiguous on both sides.  The same record
- * serves every (layer, kv) of the plan's range. */
+ * serves every (layer, kv) of the plan's range.  The convert table keeps a
+ * fixed number of slots per page of the coarser side; a slot no run claims has
+ * bytes == 0. */
 typedef struct {
     uint64_t src_off; /* pool side: page*stride_page + slot*stride_token; buffer side: T_r*bpt + t*row */
     uint64_t dst_off; /* likewise for the destination */
@@ -126,7 +129,8 @@ typedef struct {
     uint64_t token_prefix_off;                 /* uint64[R+1]: T_r, exclusive prefix sum of seq_lens */
     uint64_t run_prefix_off[3];                /* uint64[R+1] per op: first run of request r */
     uint64_t runs_off[3];                      /* kvx_run[num_runs[op]] per op */
-    uint64_t num_runs[3];                      /* op index: 0 pack, 1 unpack, 2 convert; 0 if op not planned */
+    uint64_t num_runs[3];                      /* records per op (0 pack, 1 unpack, 2 convert, empty slots
+                                                  included); 0 if the op is not planned */
 } kvx_plan_tables;
 
 /* Bytes of device workspace kvx_plan needs for these inputs.  `s`/`sb` describe

@@ -22,6 +22,7 @@ struct Geometry {
     kvx_pool_desc desc{};
     uint64_t row = 0;
     uint64_t sl = 0, sk = 0, sp = 0, st = 0; // resolved byte strides
+    bool custom_strides = false;
     uint32_t quantum = 0;                    // tokens contiguous inside a page
     uint64_t used_pages = 0;                 // sum over requests of ceil(n/P)
 };
@@ -91,6 +92,7 @@ kvx_status resolve_pool(const kvx_pool_desc *d, Geometry *g) {
         if ((d->stride_layer | d->stride_kv | d->stride_page | d->stride_token) % 16)
             return KVX_ERR_ALIGNMENT;
         if (d->stride_token < row) return KVX_ERR_INVALID_ARG;
+        g->custom_strides = true;
         g->sl = d->stride_layer;
         g->sk = d->stride_kv;
         g->sp = d->stride_page;
@@ -170,8 +172,10 @@ struct OpShape {
     bool planned = false;
     uint32_t qa = 0, qb = 0;
     uint64_t lcm = 0;
-    uint64_t num_runs = 0;
+    uint64_t num_runs = 0;       // records in the device table (for convert: slots, some empty)
     uint32_t max_run_bytes = 0;
+    uint32_t group_quantum = 0;  // convert: tokens per group = the coarser side's quantum
+    uint32_t group_slots = 1;    // convert: slots per group
 };
 
 // Sizes shared by kvx_plan_workspace_bytes and kvx_plan.
@@ -209,9 +213,18 @@ void shape_ops(const Geometry &s, const Geometry &d, const uint32_t *seq_lens, u
         uint64_t q = o.qa && o.qb ? std::min(o.qa, o.qb) : std::max(o.qa, o.qb);
         o.max_run_bytes = (uint32_t)(q * row);
         uint64_t runs = 0;
-        for (uint32_t r = 0; r < R; ++r) {
-            const uint64_t n = seq_lens[r];
-            if (n) runs += ceil_div_q(n, o.qa) + ceil_div_q(n, o.qb) - ceil_div_q(n, o.lcm);
+        if (op == OP_CONVERT) {
+            // One group per page of the coarser side, each with room for the most runs a group can hold.
+            const uint32_t coarse = std::max(o.qa, o.qb), fine = std::min(o.qa, o.qb);
+            o.group_quantum = coarse;
+            o.group_slots = coarse % fine == 0 ? coarse / fine : coarse / fine + 2;
+            for (uint32_t r = 0; r < R; ++r)
+                runs += ((uint64_t)seq_lens[r] + coarse - 1) / coarse * o.group_slots;
+        } else {
+            for (uint32_t r = 0; r < R; ++r) {
+                const uint64_t n = seq_lens[r];
+                if (n) runs += ceil_div_q(n, o.qa) + ceil_div_q(n, o.qb) - ceil_div_q(n, o.lcm);
+            }
         }
         o.num_runs = runs;
     }
@@ -281,7 +294,6 @@ namespace {
 void default_launch(kvx_launch_cfg *c) {
     if (!c->unroll) c->unroll = 1;
     if (!c->nontemporal) c->nontemporal = 2;
-    if (!c->order) c->order = 1;
     if (!c->xcd_swizzle) c->xcd_swizzle = 2;
     if (!c->max_workgroups) c->max_workgroups = 1u << 24;
     if (!c->threads) c->threads = 256;
@@ -427,6 +439,10 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
             sp.planned[op] = z.ops[op].planned;
             fp.lcm[op] = z.ops[op].lcm;
             fp.planned[op] = z.ops[op].planned;
+            if (op == OP_CONVERT) {
+                sp.group_quantum = fp.group_quantum = z.ops[op].group_quantum;
+                sp.group_slots = fp.group_slots = z.ops[op].group_slots;
+            }
             fp.run_prefix[op] = sp.prefix[SCAN_RUNS0 + op];
             fp.runs[op] = reinterpret_cast<kvx_run *>(p->ws + z.off_runs[op]);
         }
@@ -529,7 +545,13 @@ kvx_status run_op(const kvx_plan_t *plan, Op op, const void *src, void *dst, voi
     const uint32_t tile = tile_bytes(c.threads, c.unroll);
     cp.tiles_per_run = (o.max_run_bytes + tile - 1) / tile;
     cp.total_tiles = (uint32_t)((uint64_t)cp.num_lc * cp.num_runs * cp.tiles_per_run);
+    // Order of the tile space.  Unless the caller fixed it: keep the write side contiguous.  A page-major
+    // receiver holds all (layer,kv) of a page side by side, so there the run group goes outermost;
+    // everywhere else consecutive runs of a request are what is contiguous (in the buffer).
     cp.order = c.order;
+    if (!cp.order)
+        cp.order = (op != OP_PACK && !plan->d.custom_strides && plan->d.desc.layout == KVX_LAYOUT_PAGE_MAJOR) ? 2 : 1;
+    cp.group = o.group_slots;
     // keep grid * threads below 2^31 work-items; the kernel's grid-stride loop takes the rest
     const uint32_t grid_cap = std::min<uint32_t>(c.max_workgroups, (1u << 31) / c.threads - 8u);
     uint32_t grid = std::min(cp.total_tiles, grid_cap);

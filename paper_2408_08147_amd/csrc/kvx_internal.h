@@ -34,6 +34,8 @@ struct ScanParams {
     uint32_t qa[NUM_OPS], qb[NUM_OPS]; // contiguity quanta of source / destination per op (0 = buffer)
     uint64_t lcm[NUM_OPS];       // lcm(qa,qb); 0 = infinite
     uint32_t planned[NUM_OPS];
+    uint32_t group_quantum;      // convert: tokens per group (the coarser side's quantum)
+    uint32_t group_slots;        // convert: run slots reserved per group
     uint64_t *prefix[kNumScans]; // outputs
 };
 
@@ -46,6 +48,8 @@ struct FillParams {
     SideGeom src[NUM_OPS], dst[NUM_OPS];
     uint64_t lcm[NUM_OPS];
     uint32_t planned[NUM_OPS];
+    uint32_t group_quantum;      // convert only, as in ScanParams
+    uint32_t group_slots;
     const uint64_t *run_prefix[NUM_OPS];
     kvx_run *runs[NUM_OPS];
 };
@@ -63,7 +67,8 @@ struct CopyParams {
     uint32_t num_runs;
     uint32_t tiles_per_run;
     uint32_t total_tiles;     // num_lc * num_runs * tiles_per_run
-    uint32_t order;           // 1: (layer,kv) outermost   2: run outermost
+    uint32_t order;           // 1: (layer,kv) outermost   2: run group outermost
+    uint32_t group;           // order 2: consecutive runs that stay together inside one (layer,kv)
     uint32_t swizzle_chunk;   // 0 = off, else tiles per XCD (grid is a multiple of 8)
 };
 

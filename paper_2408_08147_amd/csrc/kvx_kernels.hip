@@ -6,7 +6,10 @@
 //                a single workgroup.  These are the offsets section 3.6 of the
 //                paper derives from prompt length, hidden size and precision.
 //   fill_kernel  writes the flat copy plan: one kvx_run per maximal span of
-//                tokens that is contiguous on both sides of an operation.
+//                tokens that is contiguous on both sides of an operation.  For
+//                convert the runs are laid out in groups of a fixed number of
+//                slots, one group per page of the coarser side, so that the
+//                data mover can keep a group together.
 //   copy_kernel  the pack / unpack / convert data mover: every workgroup takes
 //                tiles of (run, layer, K|V) and moves them with 16-byte loads
 //                and stores, all loads of a tile in flight before its first
@@ -60,6 +63,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanParams p) {
 #pragma unroll
             for (int op = 0; op < (int)NUM_OPS; ++op)
                 v[SCAN_RUNS0 + op] = p.planned[op] ? count_runs(n, p.qa[op], p.qb[op], p.lcm[op]) : 0;
+            if (p.planned[OP_CONVERT]) // slots, not runs: a fixed number per group
+                v[SCAN_RUNS0 + OP_CONVERT] = (n + p.group_quantum - 1) / p.group_quantum * p.group_slots;
         }
         uint64_t inc[kNumScans];
 #pragma unroll
@@ -119,6 +124,14 @@ __global__ __launch_bounds__(kFillThreads) void fill_kernel(FillParams p) {
         const uint64_t cb = ceil_div_q(n, b.quantum);
         const uint64_t buf_base = p.token_prefix[r] * p.bytes_per_token;
         kvx_run *out = p.runs[op] + p.run_prefix[op][r];
+        const bool grouped = (op == OP_CONVERT);
+        if (grouped) {
+            // slots that no run claims must read as empty (bytes == 0)
+            const uint64_t slots = p.run_prefix[op][r + 1] - p.run_prefix[op][r];
+            kvx_run none{};
+            for (uint64_t i = threadIdx.x; i < slots; i += kFillThreads) out[i] = none;
+            __syncthreads();
+        }
         for (uint64_t i = threadIdx.x; i < ca + cb; i += kFillThreads) {
             uint64_t x;
             if (i < ca) {
@@ -128,7 +141,14 @@ __global__ __launch_bounds__(kFillThreads) void fill_kernel(FillParams p) {
                 const bool also_a = a.quantum ? (x % a.quantum == 0) : (x == 0);
                 if (also_a) continue; // that boundary belongs to the other side's thread
             }
-            const uint64_t rank = ceil_div_q(x, a.quantum) + ceil_div_q(x, b.quantum) - ceil_div_q(x, l);
+            uint64_t rank = ceil_div_q(x, a.quantum) + ceil_div_q(x, b.quantum) - ceil_div_q(x, l);
+            if (grouped) {
+                // position = group * slots + rank among the boundaries inside the group
+                const uint64_t g = x / p.group_quantum;
+                const uint64_t g0 = g * p.group_quantum;
+                rank = g * p.group_slots + rank -
+                       (ceil_div_q(g0, a.quantum) + ceil_div_q(g0, b.quantum) - ceil_div_q(g0, l));
+            }
             uint64_t end = n;
             if (a.quantum) end = min(end, (x / a.quantum + 1) * a.quantum);
             if (b.quantum) end = min(end, (x / b.quantum + 1) * b.quantum);
@@ -174,8 +194,10 @@ __global__ __launch_bounds__(T) void copy_kernel(const kvx_run *__restrict__ run
         const uint32_t s = v % p.tiles_per_run;
         const uint32_t q = v / p.tiles_per_run;
         if (p.order == 2) {
-            lc = q % p.num_lc;
-            e = q / p.num_lc;
+            const uint32_t i = q % p.group;
+            const uint32_t q2 = q / p.group;
+            lc = q2 % p.num_lc;
+            e = (q2 / p.num_lc) * p.group + i;
         } else {
             e = q % p.num_runs;
             lc = q / p.num_runs;

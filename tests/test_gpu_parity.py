@@ -88,6 +88,7 @@ def test_explicit_strides_padded_rows_and_pages():
     dict(unroll=2, max_workgroups=7), dict(unroll=4, nontemporal=1, max_workgroups=1),
     dict(threads=64), dict(threads=128, unroll=2, xcd_swizzle=1), dict(threads=512, unroll=4, order=2),
     dict(threads=1024, unroll=8), dict(threads=1024, unroll=1, max_workgroups=16),
+    dict(order=1), dict(order=2, xcd_swizzle=1), dict(order=2, threads=512, unroll=4),
 ])
 def test_results_do_not_depend_on_launch_config(launch):
     rng = np.random.default_rng(7)
@@ -148,20 +149,31 @@ def test_device_plan_tables(Ps, Pd):
         runs, pre = res.extra[f"runs{op}"], res.extra[f"run_prefix{op}"]
         assert pre[0] == 0 and pre[-1] == len(runs)
         assert np.all(np.diff(pre.astype(np.int64)) >= 0)
-        req = np.repeat(np.arange(len(lens)), np.diff(pre.astype(np.int64)))
-        assert np.array_equal(runs["request"], req)
+        owner = np.repeat(np.arange(len(lens)), np.diff(pre.astype(np.int64)))
+        if op == 2:
+            # convert keeps a fixed number of slots per page of the coarser side; unclaimed slots are empty
+            coarse, fine = max(Ps, Pd), min(Ps, Pd)
+            slots = coarse // fine if coarse % fine == 0 else coarse // fine + 2
+            pages = (lens.astype(np.int64) + coarse - 1) // coarse
+            assert np.array_equal(np.diff(pre.astype(np.int64)), pages * slots)
+            live = runs["bytes"] > 0
+            assert np.all(runs["token"][live] // coarse == (np.arange(len(runs))[live] - pre[owner[live]]) // slots)
+            runs, owner = runs[live], owner[live]
+        req = runs["request"].astype(np.int64)
+        assert np.array_equal(req, owner)
         assert np.array_equal(runs["seq_len"], lens[req])
         tok, ntok = runs["token"].astype(np.int64), runs["bytes"].astype(np.int64) // row
         assert np.all(runs["bytes"] % row == 0) and np.all(ntok > 0)
-        first = np.zeros(len(runs), dtype=bool)
-        first[pre[:-1][np.diff(pre.astype(np.int64)) > 0]] = True
-        assert np.all(tok[first] == 0)
         nxt = tok + ntok
         same_req = req[1:] == req[:-1]
+        first = np.ones(len(runs), dtype=bool)
+        first[1:] = ~same_req
+        assert np.all(tok[first] == 0)
         assert np.all(tok[1:][same_req] == nxt[:-1][same_req])                 # contiguous inside a request
         last = np.ones(len(runs), dtype=bool)
         last[:-1] = ~same_req
         assert np.array_equal(nxt[last], lens[req[last]].astype(np.int64))     # and they end at n_r
+        assert np.array_equal(np.unique(req), np.flatnonzero(lens))           # every non-empty request is there
         for q in (qa, qb):
             if q:
                 assert np.all(tok // q == (nxt - 1) // q)                      # never crosses a page
