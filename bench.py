@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per copy_kernel launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by the plain-copy calibration), valid only for the kernel source they were taken on.
 COUNTER_RUNS = {
-    2: {"kernels_sha256": "3409cbe615b68ae50c241a78f1f9fbb846131c8049c83c1c8610489faf5abbb0",
-        "traffic_bytes_per_launch": 12099243516},
+    2: {"kernels_sha256": "b1aba360623ee34871f620ba867da6fb4c98625125cc6c902bef8d8a53ac6c9a",
+        "traffic_bytes_per_launch": 12099303556},
 }
 
 

@@ -291,12 +291,25 @@ struct kvx_plan_s {
 };
 
 namespace {
+// Fields the library fills at once; order, threads and unroll stay 0 (= chosen per operation at launch).
 void default_launch(kvx_launch_cfg *c) {
-    if (!c->unroll) c->unroll = 1;
     if (!c->nontemporal) c->nontemporal = 2;
     if (!c->xcd_swizzle) c->xcd_swizzle = 2;
     if (!c->max_workgroups) c->max_workgroups = 1u << 24;
-    if (!c->threads) c->threads = 256;
+}
+
+// Tile shape when the caller left it open.  Measured on MI355X: with (layer,kv) outermost the smallest
+// tile (256 lanes x 16 B) with the largest grid is fastest; with the run group outermost (page-major
+// receiver) one workgroup per whole run, up to 512 lanes x 4 x 16 B = 32 KiB, is.
+void resolve_tile(uint32_t order, uint32_t max_run_bytes, uint32_t *threads, uint32_t *unroll) {
+    if (*threads && *unroll) return;
+    uint32_t t = 256, u = 1;
+    if (order == 2) {
+        t = 512;
+        while (u < 4 && tile_bytes(t, u * 2) <= max_run_bytes) u *= 2;
+    }
+    if (!*threads) *threads = t;
+    if (!*unroll) *unroll = u;
 }
 } // namespace
 
@@ -505,8 +518,10 @@ kvx_status kvx_plan_set_launch(kvx_plan_t *plan, const kvx_launch_cfg *cfg) {
     if (!plan || !cfg) return KVX_ERR_INVALID_ARG;
     kvx_launch_cfg c = *cfg;
     default_launch(&c);
-    if (!valid_unroll(c.unroll) || !valid_threads(c.threads)) return KVX_ERR_INVALID_ARG;
-    if (c.nontemporal > 2 || c.order > 2 || c.xcd_swizzle > 2) return KVX_ERR_INVALID_ARG;
+    if ((c.unroll && !valid_unroll(c.unroll)) || (c.threads && !valid_threads(c.threads)))
+        return KVX_ERR_INVALID_ARG;
+    if (c.nontemporal > 2 || c.order > 2 || c.xcd_swizzle > 2 || c.workgroups_per_cu > 8)
+        return KVX_ERR_INVALID_ARG;
     plan->launch = c;
     return KVX_OK;
 }
@@ -542,9 +557,6 @@ kvx_status run_op(const kvx_plan_t *plan, Op op, const void *src, void *dst, voi
     cp.layer_begin = plan->l0;
     cp.num_lc = 2 * (plan->l1 - plan->l0);
     cp.num_runs = (uint32_t)o.num_runs;
-    const uint32_t tile = tile_bytes(c.threads, c.unroll);
-    cp.tiles_per_run = (o.max_run_bytes + tile - 1) / tile;
-    cp.total_tiles = (uint32_t)((uint64_t)cp.num_lc * cp.num_runs * cp.tiles_per_run);
     // Order of the tile space.  Unless the caller fixed it: keep the write side contiguous.  A page-major
     // receiver holds all (layer,kv) of a page side by side, so there the run group goes outermost;
     // everywhere else consecutive runs of a request are what is contiguous (in the buffer).
@@ -552,14 +564,19 @@ kvx_status run_op(const kvx_plan_t *plan, Op op, const void *src, void *dst, voi
     if (!cp.order)
         cp.order = (op != OP_PACK && !plan->d.custom_strides && plan->d.desc.layout == KVX_LAYOUT_PAGE_MAJOR) ? 2 : 1;
     cp.group = o.group_slots;
+    uint32_t threads = c.threads, unroll = c.unroll;
+    resolve_tile(cp.order, o.max_run_bytes, &threads, &unroll);
+    const uint32_t tile = tile_bytes(threads, unroll);
+    cp.tiles_per_run = (o.max_run_bytes + tile - 1) / tile;
+    cp.total_tiles = (uint32_t)((uint64_t)cp.num_lc * cp.num_runs * cp.tiles_per_run);
     // keep grid * threads below 2^31 work-items; the kernel's grid-stride loop takes the rest
-    const uint32_t grid_cap = std::min<uint32_t>(c.max_workgroups, (1u << 31) / c.threads - 8u);
+    const uint32_t grid_cap = std::min<uint32_t>(c.max_workgroups, (1u << 31) / threads - 8u);
     uint32_t grid = std::min(cp.total_tiles, grid_cap);
     if (c.xcd_swizzle == 2) {
         grid = (grid + 7u) / 8u * 8u;
         cp.swizzle_chunk = grid / 8u;
     }
-    hipError_t e = launch_copy(cp, c.threads, c.unroll, c.nontemporal == 2, grid,
+    hipError_t e = launch_copy(cp, threads, unroll, c.nontemporal == 2, grid, occupancy_lds(c.workgroups_per_cu),
                                static_cast<hipStream_t>(stream));
     return e == hipSuccess ? KVX_OK : KVX_ERR_DEVICE;
 }
@@ -594,6 +611,7 @@ kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const 
     kvx_launch_cfg c{};
     if (cfg) c = *cfg;
     default_launch(&c);
+    resolve_tile(1, 0, &c.threads, &c.unroll);
     if (!valid_unroll(c.unroll) || !valid_threads(c.threads)) return KVX_ERR_INVALID_ARG;
     hipError_t e = launch_plain_copy(static_cast<char *>(dst), static_cast<const char *>(src), bytes, c.threads,
                                      c.unroll,

@@ -79,7 +79,12 @@ inline bool valid_unroll(uint32_t u) { return u == 1 || u == 2 || u == 4 || u ==
 hipError_t launch_scan(const ScanParams &p, hipStream_t stream);
 hipError_t launch_fill(const FillParams &p, hipStream_t stream);
 hipError_t launch_copy(const CopyParams &p, uint32_t threads, uint32_t unroll, bool nontemporal, uint32_t grid,
-                       hipStream_t stream);
+                       uint32_t lds_bytes, hipStream_t stream);
+
+// LDS per compute unit on gfx950, and the unused dynamic LDS to reserve per workgroup so that at most
+// `per_cu` workgroups are resident on a compute unit (0 = no cap).
+constexpr uint32_t kLdsPerCu = 160u * 1024u;
+inline uint32_t occupancy_lds(uint32_t per_cu) { return per_cu ? kLdsPerCu / per_cu / 1024u * 1024u : 0u; }
 
 hipError_t launch_plain_copy(char *dst, const char *src, uint64_t bytes, uint32_t threads, uint32_t unroll,
                              bool nontemporal, uint32_t max_wg, hipStream_t stream);

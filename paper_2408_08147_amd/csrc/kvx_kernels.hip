@@ -280,20 +280,34 @@ hipError_t launch_fill(const FillParams &p, hipStream_t stream) {
 namespace {
 
 // Dispatch of the runtime (threads, unroll, nontemporal) triple to a template instance.
-template <int T, int U>
-hipError_t copy_tu(const CopyParams &p, bool nt, uint32_t grid, hipStream_t stream) {
-    if (nt) hipLaunchKernelGGL((copy_kernel<T, U, true>), dim3(grid), dim3(T), 0, stream, p.runs, p.src, p.dst, p);
-    else hipLaunchKernelGGL((copy_kernel<T, U, false>), dim3(grid), dim3(T), 0, stream, p.runs, p.src, p.dst, p);
+// `lds` bytes of dynamic LDS are reserved and never touched: they only cap the workgroups per compute unit.
+template <int T, int U, bool NT>
+hipError_t copy_tun(const CopyParams &p, uint32_t grid, uint32_t lds, hipStream_t stream) {
+    if (lds > 64u * 1024u) {
+        static bool raised = false; // per instantiation; the attribute is sticky
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&copy_kernel<T, U, NT>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL((copy_kernel<T, U, NT>), dim3(grid), dim3(T), lds, stream, p.runs, p.src, p.dst, p);
     return hipGetLastError();
 }
 
+template <int T, int U>
+hipError_t copy_tu(const CopyParams &p, bool nt, uint32_t grid, uint32_t lds, hipStream_t stream) {
+    return nt ? copy_tun<T, U, true>(p, grid, lds, stream) : copy_tun<T, U, false>(p, grid, lds, stream);
+}
+
 template <int T>
-hipError_t copy_t(const CopyParams &p, uint32_t unroll, bool nt, uint32_t grid, hipStream_t stream) {
+hipError_t copy_t(const CopyParams &p, uint32_t unroll, bool nt, uint32_t grid, uint32_t lds, hipStream_t stream) {
     switch (unroll) {
-    case 1: return copy_tu<T, 1>(p, nt, grid, stream);
-    case 2: return copy_tu<T, 2>(p, nt, grid, stream);
-    case 4: return copy_tu<T, 4>(p, nt, grid, stream);
-    case 8: return copy_tu<T, 8>(p, nt, grid, stream);
+    case 1: return copy_tu<T, 1>(p, nt, grid, lds, stream);
+    case 2: return copy_tu<T, 2>(p, nt, grid, lds, stream);
+    case 4: return copy_tu<T, 4>(p, nt, grid, lds, stream);
+    case 8: return copy_tu<T, 8>(p, nt, grid, lds, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -324,14 +338,14 @@ hipError_t plain_t(char *dst, const char *src, uint64_t bytes, uint32_t unroll, 
 } // namespace
 
 hipError_t launch_copy(const CopyParams &p, uint32_t threads, uint32_t unroll, bool nontemporal, uint32_t grid,
-                       hipStream_t stream) {
+                       uint32_t lds_bytes, hipStream_t stream) {
     if (p.total_tiles == 0 || grid == 0) return hipSuccess;
     switch (threads) {
-    case 64: return copy_t<64>(p, unroll, nontemporal, grid, stream);
-    case 128: return copy_t<128>(p, unroll, nontemporal, grid, stream);
-    case 256: return copy_t<256>(p, unroll, nontemporal, grid, stream);
-    case 512: return copy_t<512>(p, unroll, nontemporal, grid, stream);
-    case 1024: return copy_t<1024>(p, unroll, nontemporal, grid, stream);
+    case 64: return copy_t<64>(p, unroll, nontemporal, grid, lds_bytes, stream);
+    case 128: return copy_t<128>(p, unroll, nontemporal, grid, lds_bytes, stream);
+    case 256: return copy_t<256>(p, unroll, nontemporal, grid, lds_bytes, stream);
+    case 512: return copy_t<512>(p, unroll, nontemporal, grid, lds_bytes, stream);
+    case 1024: return copy_t<1024>(p, unroll, nontemporal, grid, lds_bytes, stream);
     default: return hipErrorInvalidValue;
     }
 }
