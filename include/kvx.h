@@ -102,12 +102,13 @@ typedef struct {
     uint32_t nontemporal;   /* 1 = off, 2 = non-temporal loads and stores */
     uint32_t order;         /* 0 = chosen per operation from the receiver's layout, 1 = (layer,kv) outermost,
                                2 = copy run (for convert: group of runs) outermost */
-    uint32_t xcd_swizzle;   /* 1 = off, 2 = give each of the 8 XCDs a contiguous range of tiles */
+    uint32_t xcd_swizzle;   /* 1 = off, 2 = give each of the 8 XCDs contiguous tiles: one eighth of the grid
+                               each, or blocks of `xcd_block_tiles` tiles dealt round-robin */
     uint32_t max_workgroups;/* cap on the grid; tiles beyond it are taken in a grid-stride loop */
     uint32_t threads;       /* lanes per workgroup: 64, 128, 256, 512 or 1024; a tile is threads*16*unroll bytes */
     uint32_t workgroups_per_cu; /* 0 = as many as fit; n = at most n resident per compute unit (1..8), which
                                bounds the bytes in flight; done by reserving unused LDS per workgroup */
-    uint32_t reserved[1];
+    uint32_t xcd_block_tiles; /* with xcd_swizzle 2: 0 = eighths of the grid, else a power of two */
 } kvx_launch_cfg;
 
 typedef struct kvx_plan_s kvx_plan_t;

@@ -522,6 +522,7 @@ kvx_status kvx_plan_set_launch(kvx_plan_t *plan, const kvx_launch_cfg *cfg) {
         return KVX_ERR_INVALID_ARG;
     if (c.nontemporal > 2 || c.order > 2 || c.xcd_swizzle > 2 || c.workgroups_per_cu > 8)
         return KVX_ERR_INVALID_ARG;
+    if (c.xcd_block_tiles & (c.xcd_block_tiles - 1u) || c.xcd_block_tiles > 4096u) return KVX_ERR_INVALID_ARG;
     plan->launch = c;
     return KVX_OK;
 }
@@ -573,8 +574,12 @@ kvx_status run_op(const kvx_plan_t *plan, Op op, const void *src, void *dst, voi
     const uint32_t grid_cap = std::min<uint32_t>(c.max_workgroups, (1u << 31) / threads - 8u);
     uint32_t grid = std::min(cp.total_tiles, grid_cap);
     if (c.xcd_swizzle == 2) {
-        grid = (grid + 7u) / 8u * 8u;
+        const uint32_t unit = 8u * std::max(c.xcd_block_tiles, 1u);
+        grid = (grid + unit - 1u) / unit * unit; // the tile map is a bijection on a grid of whole units
+        const uint32_t limit = (1u << 31) / threads;
+        if (grid > limit) grid = limit / unit * unit;
         cp.swizzle_chunk = grid / 8u;
+        cp.swizzle_block = c.xcd_block_tiles;
     }
     hipError_t e = launch_copy(cp, threads, unroll, c.nontemporal == 2, grid, occupancy_lds(c.workgroups_per_cu),
                                static_cast<hipStream_t>(stream));

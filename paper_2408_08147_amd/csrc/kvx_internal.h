@@ -70,6 +70,7 @@ struct CopyParams {
     uint32_t order;           // 1: (layer,kv) outermost   2: run group outermost
     uint32_t group;           // order 2: consecutive runs that stay together inside one (layer,kv)
     uint32_t swizzle_chunk;   // 0 = off, else tiles per XCD (grid is a multiple of 8)
+    uint32_t swizzle_block;   // 0 = eighths of the grid, else tiles per block dealt round-robin to the XCDs
 };
 
 inline uint32_t tile_bytes(uint32_t threads, uint32_t unroll) { return threads * 16u * unroll; }

@@ -185,8 +185,14 @@ __global__ __launch_bounds__(T) void copy_kernel(const kvx_run *__restrict__ run
     constexpr uint32_t kTile = kStep * U;
     const uint32_t lane_off = threadIdx.x * 16u;
 
+    // Workgroup b runs on XCD b mod 8 and is the (b div 8)-th one there.
     uint32_t first = blockIdx.x;
-    if (p.swizzle_chunk) first = (blockIdx.x & 7u) * p.swizzle_chunk + (blockIdx.x >> 3);
+    if (p.swizzle_block) {
+        const uint32_t j = blockIdx.x >> 3, k = blockIdx.x & 7u;
+        first = (j / p.swizzle_block) * (8u * p.swizzle_block) + k * p.swizzle_block + (j % p.swizzle_block);
+    } else if (p.swizzle_chunk) {
+        first = (blockIdx.x & 7u) * p.swizzle_chunk + (blockIdx.x >> 3);
+    }
 
     for (uint64_t v64 = first; v64 < p.total_tiles; v64 += gridDim.x) {
         const uint32_t v = (uint32_t)v64;

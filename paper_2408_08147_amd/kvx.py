@@ -57,7 +57,7 @@ class _BatchDesc(C.Structure):
 class LaunchCfg(C.Structure):
     _fields_ = [("unroll", C.c_uint32), ("nontemporal", C.c_uint32), ("order", C.c_uint32),
                 ("xcd_swizzle", C.c_uint32), ("max_workgroups", C.c_uint32),
-                ("threads", C.c_uint32), ("workgroups_per_cu", C.c_uint32), ("reserved", C.c_uint32 * 1)]
+                ("threads", C.c_uint32), ("workgroups_per_cu", C.c_uint32), ("xcd_block_tiles", C.c_uint32)]
 
 
 class PlanTables(C.Structure):
@@ -212,8 +212,9 @@ def kvx_plan_get_tables(plan: Plan) -> PlanTables:
 
 def kvx_plan_set_launch(plan: Plan, unroll: int = 0, nontemporal: int = 0, order: int = 0,
                         xcd_swizzle: int = 0, max_workgroups: int = 0, threads: int = 0,
-                        workgroups_per_cu: int = 0) -> None:
-    cfg = LaunchCfg(unroll, nontemporal, order, xcd_swizzle, max_workgroups, threads, workgroups_per_cu)
+                        workgroups_per_cu: int = 0, xcd_block_tiles: int = 0) -> None:
+    cfg = LaunchCfg(unroll, nontemporal, order, xcd_swizzle, max_workgroups, threads, workgroups_per_cu,
+                    xcd_block_tiles)
     _check(load().kvx_plan_set_launch(plan.handle, C.byref(cfg)), "kvx_plan_set_launch")
 
 
