@@ -210,6 +210,21 @@ kvx_status kvx_unpack(const kvx_plan_t *plan, const void *buf, uint64_t buf_byte
  * overlap. */
 kvx_status kvx_convert(const kvx_plan_t *plan, const void *src_pool, void *dst_pool, void *stream);
 
+/* Per-layer triggers (section 3.6: either the transfer per layer or of the
+ * entire model, by different offsets and lengths into the same buffer; the
+ * "operator" form of RecvScatter that runs between a model's layers).  Same as
+ * kvx_pack / kvx_unpack / kvx_convert, restricted to layers
+ * [layer_begin, layer_end) of the plan's range: exactly those layers' segments
+ * of the plan's buffer (kvx_plan_segment) are written or read, at the offsets
+ * of the whole-range buffer, so one plan and one buffer serve every layer.
+ * A range outside the plan's is KVX_ERR_INVALID_ARG; an empty one is a no-op. */
+kvx_status kvx_pack_layers(const kvx_plan_t *plan, uint32_t layer_begin, uint32_t layer_end,
+                           const void *src_pool, void *buf, uint64_t buf_bytes, void *stream);
+kvx_status kvx_unpack_layers(const kvx_plan_t *plan, uint32_t layer_begin, uint32_t layer_end, const void *buf,
+                             uint64_t buf_bytes, void *dst_pool, void *stream);
+kvx_status kvx_convert_layers(const kvx_plan_t *plan, uint32_t layer_begin, uint32_t layer_end,
+                              const void *src_pool, void *dst_pool, void *stream);
+
 /* Yardstick, not part of the transfer: a plain contiguous device-to-device copy
  * of `bytes` bytes (a multiple of 16; both pointers [device], 16-byte aligned,
  * not overlapping) made of the same 16-byte loads and stores as the data

@@ -537,10 +537,14 @@ kvx_status kvx_plan_get_launch(const kvx_plan_t *plan, kvx_launch_cfg *out) {
 
 namespace {
 
-kvx_status run_op(const kvx_plan_t *plan, Op op, const void *src, void *dst, void *stream) {
+// Launches one operation over layers [lb, le) of the plan's range.  Buffer offsets stay those of the
+// plan's whole range, so a sub-range touches exactly its own segments of the same buffer.
+kvx_status run_op(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, const void *src, void *dst,
+                  void *stream) {
     const OpShape &o = plan->z.ops[op];
     if (!plan->ws || !o.planned) return KVX_ERR_INVALID_ARG;
-    if (plan->total == 0) return KVX_OK;
+    if (lb > le || lb < plan->l0 || le > plan->l1) return KVX_ERR_INVALID_ARG;
+    if (plan->total == 0 || lb == le) return KVX_OK;
     if (!src || !dst) return KVX_ERR_INVALID_ARG;
     if (((uintptr_t)src | (uintptr_t)dst) % 16) return KVX_ERR_ALIGNMENT;
     const kvx_launch_cfg &c = plan->launch;
@@ -556,7 +560,8 @@ kvx_status run_op(const kvx_plan_t *plan, Op op, const void *src, void *dst, voi
     cp.dst_stride_kv = plan->d.sk;
     cp.row = (uint32_t)plan->row;
     cp.layer_begin = plan->l0;
-    cp.num_lc = 2 * (plan->l1 - plan->l0);
+    cp.lc_first = 2 * (lb - plan->l0);
+    cp.num_lc = 2 * (le - lb);
     cp.num_runs = (uint32_t)o.num_runs;
     // Order of the tile space.  Unless the caller fixed it: keep the write side contiguous.  A page-major
     // receiver holds all (layer,kv) of a page side by side, so there the run group goes outermost;
@@ -594,19 +599,39 @@ kvx_status kvx_pack(const kvx_plan_t *plan, const void *src_pool, void *buf, uin
                     void *stream) {
     if (!plan) return KVX_ERR_INVALID_ARG;
     if (buf_bytes < plan->total) return KVX_ERR_CAPACITY;
-    return run_op(plan, OP_PACK, src_pool, buf, stream);
+    return run_op(plan, OP_PACK, plan->l0, plan->l1, src_pool, buf, stream);
 }
 
 kvx_status kvx_unpack(const kvx_plan_t *plan, const void *buf, uint64_t buf_bytes, void *dst_pool,
                       void *stream) {
     if (!plan) return KVX_ERR_INVALID_ARG;
     if (buf_bytes < plan->total) return KVX_ERR_CAPACITY;
-    return run_op(plan, OP_UNPACK, buf, dst_pool, stream);
+    return run_op(plan, OP_UNPACK, plan->l0, plan->l1, buf, dst_pool, stream);
 }
 
 kvx_status kvx_convert(const kvx_plan_t *plan, const void *src_pool, void *dst_pool, void *stream) {
     if (!plan) return KVX_ERR_INVALID_ARG;
-    return run_op(plan, OP_CONVERT, src_pool, dst_pool, stream);
+    return run_op(plan, OP_CONVERT, plan->l0, plan->l1, src_pool, dst_pool, stream);
+}
+
+kvx_status kvx_pack_layers(const kvx_plan_t *plan, uint32_t layer_begin, uint32_t layer_end,
+                           const void *src_pool, void *buf, uint64_t buf_bytes, void *stream) {
+    if (!plan) return KVX_ERR_INVALID_ARG;
+    if (buf_bytes < plan->total) return KVX_ERR_CAPACITY;
+    return run_op(plan, OP_PACK, layer_begin, layer_end, src_pool, buf, stream);
+}
+
+kvx_status kvx_unpack_layers(const kvx_plan_t *plan, uint32_t layer_begin, uint32_t layer_end, const void *buf,
+                             uint64_t buf_bytes, void *dst_pool, void *stream) {
+    if (!plan) return KVX_ERR_INVALID_ARG;
+    if (buf_bytes < plan->total) return KVX_ERR_CAPACITY;
+    return run_op(plan, OP_UNPACK, layer_begin, layer_end, buf, dst_pool, stream);
+}
+
+kvx_status kvx_convert_layers(const kvx_plan_t *plan, uint32_t layer_begin, uint32_t layer_end,
+                              const void *src_pool, void *dst_pool, void *stream) {
+    if (!plan) return KVX_ERR_INVALID_ARG;
+    return run_op(plan, OP_CONVERT, layer_begin, layer_end, src_pool, dst_pool, stream);
 }
 
 kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const kvx_launch_cfg *cfg,

@@ -62,8 +62,9 @@ struct CopyParams {
     uint64_t dst_stride_layer, dst_stride_kv;
     uint32_t src_is_buf, dst_is_buf;
     uint32_t row;
-    uint32_t layer_begin;
-    uint32_t num_lc;          // 2 * layers in range
+    uint32_t layer_begin;     // first layer of the plan's range: buffer offsets are relative to it
+    uint32_t lc_first;        // first (layer,kv) index of this launch inside the plan's range
+    uint32_t num_lc;          // 2 * layers of this launch
     uint32_t num_runs;
     uint32_t tiles_per_run;
     uint32_t total_tiles;     // num_lc * num_runs * tiles_per_run

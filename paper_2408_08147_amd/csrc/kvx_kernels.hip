@@ -208,6 +208,7 @@ __global__ __launch_bounds__(T) void copy_kernel(const kvx_run *__restrict__ run
             e = q % p.num_runs;
             lc = q / p.num_runs;
         }
+        lc += p.lc_first;
         const kvx_run run = runs[e];
         const uint32_t base = s * kTile;
         if (base >= run.bytes) continue;

@@ -1,0 +1,109 @@
+"""Per-layer triggers: kvx_pack_layers / kvx_unpack_layers / kvx_convert_layers
+touch exactly the chosen layers' segments of the whole-range buffer (and the
+chosen layers of the receiver's pool) and nothing else.  Expected bytes come
+from the oracle run on one-layer ranges, placed at the whole-range `segment`
+offsets (section 3.6: per-layer or whole-model transfer into the same buffer)."""
+import numpy as np
+import pytest
+
+from oracle import kvxo
+from paper_2408_08147_amd import kvx
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def setup_case(ls, ld, Ps, Pd):
+    rng = np.random.default_rng(31 + Ps + Pd)
+    case = G.make_case(rng, 5, 2, 64, 2, [300, 0, 17, 129, 1000, 64], Ps, Pd, ls, ld)
+    src = rng.integers(0, 256, size=case.pool_bytes(case.s), dtype=np.uint8)
+    return case, src
+
+
+@pytest.mark.parametrize("ls,ld,Ps,Pd", [(0, 0, 16, 16), (0, 1, 128, 16), (1, 0, 8, 24)])
+def test_layer_subranges_touch_only_their_segments(ls, ld, Ps, Pd):
+    import torch
+    case, src = setup_case(ls, ld, Ps, Pd)
+    L0, L1 = 1, 5                                  # the plan's range does not start at layer 0
+    picks = [(2, 3), (4, 5)]
+    ps, pd = case.oracle_pool(case.s), case.oracle_pool(case.d)
+    bs = kvxo.Batch(case.seq_lens, case.ids_s, case.offs_s)
+    bd = kvxo.Batch(case.seq_lens, case.ids_d, case.offs_d)
+    total = kvxo.total_bytes(ps, bs, L0, L1)
+    R = len(case.seq_lens)
+
+    # expected: canaries, plus one-layer oracle results at whole-range segment offsets
+    want_buf = np.full(total + G.BUF_SLACK, G.CANARY_BUF, dtype=np.uint8)
+    full_buf = np.zeros(total, dtype=np.uint8)
+    kvxo.pack(ps, bs, L0, L1, src, full_buf)
+    want_unpack = np.full(case.pool_bytes(case.d), G.CANARY_POOL, dtype=np.uint8)
+    want_convert = want_unpack.copy()
+    for lb, le in picks:
+        for l in range(lb, le):
+            part = np.zeros(kvxo.total_bytes(ps, bs, l, l + 1), dtype=np.uint8)
+            kvxo.pack(ps, bs, l, l + 1, src, part)
+            for r in range(R):
+                ow, nw = kvxo.segment(ps, bs, L0, L1, r, l)
+                op, n1 = kvxo.segment(ps, bs, l, l + 1, r, l)
+                want_buf[ow:ow + nw] = part[op:op + n1]
+            kvxo.unpack(pd, bd, l, l + 1, part, want_unpack)
+            kvxo.convert(ps, bs, pd, bd, l, l + 1, src, want_convert)
+
+    dev = torch.device("cuda:0")
+    st = torch.cuda.Stream(device=dev)
+    sp, dp = case.kvx_pool(case.s), case.kvx_pool(case.d)
+    sb = kvx.BatchDesc(case.seq_lens, case.ids_s, case.offs_s)
+    db = kvx.BatchDesc(case.seq_lens, case.ids_d, case.offs_d)
+    nws = kvx.kvx_plan_workspace_bytes(sp, sb, dp, db)
+    with torch.cuda.stream(st):
+        ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+        src_t = torch.from_numpy(src).to(dev)
+        full_t = torch.from_numpy(full_buf).to(dev)
+        plan = kvx.kvx_plan(sp, sb, dp, db, L0, L1, ws.data_ptr(), nws, st.cuda_stream)
+        assert kvx.kvx_plan_total_bytes(plan) == total
+        buf = torch.full((total + G.BUF_SLACK,), G.CANARY_BUF, dtype=torch.uint8, device=dev)
+        du = torch.full((case.pool_bytes(case.d),), G.CANARY_POOL, dtype=torch.uint8, device=dev)
+        dc = torch.full((case.pool_bytes(case.d),), G.CANARY_POOL, dtype=torch.uint8, device=dev)
+        for lb, le in picks:
+            kvx.kvx_pack_layers(plan, lb, le, src_t.data_ptr(), buf.data_ptr(), total, st.cuda_stream)
+            kvx.kvx_unpack_layers(plan, lb, le, full_t.data_ptr(), total, du.data_ptr(), st.cuda_stream)
+            kvx.kvx_convert_layers(plan, lb, le, src_t.data_ptr(), dc.data_ptr(), st.cuda_stream)
+        kvx.kvx_pack_layers(plan, 3, 3, src_t.data_ptr(), buf.data_ptr(), total, st.cuda_stream)   # empty: no-op
+    st.synchronize()
+    assert np.array_equal(buf.cpu().numpy(), want_buf)
+    assert np.array_equal(du.cpu().numpy(), want_unpack)
+    assert np.array_equal(dc.cpu().numpy(), want_convert)
+
+    for bad in [(0, 2), (4, 6), (3, 2)]:
+        with pytest.raises(kvx.KvxError) as e:
+            kvx.kvx_pack_layers(plan, bad[0], bad[1], src_t.data_ptr(), buf.data_ptr(), total, st.cuda_stream)
+        assert e.value.status == kvx.ERR_INVALID_ARG
+    plan.destroy()
+
+
+def test_all_layers_one_by_one_equal_the_whole():
+    import torch
+    case, src = setup_case(0, 1, 32, 16)
+    want = G.run_oracle(case, src, 0, case.num_layers)
+    dev = torch.device("cuda:0")
+    st = torch.cuda.Stream(device=dev)
+    sp, dp = case.kvx_pool(case.s), case.kvx_pool(case.d)
+    sb = kvx.BatchDesc(case.seq_lens, case.ids_s, case.offs_s)
+    db = kvx.BatchDesc(case.seq_lens, case.ids_d, case.offs_d)
+    nws = kvx.kvx_plan_workspace_bytes(sp, sb, dp, db)
+    with torch.cuda.stream(st):
+        ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+        src_t = torch.from_numpy(src).to(dev)
+        plan = kvx.kvx_plan(sp, sb, dp, db, 0, case.num_layers, ws.data_ptr(), nws, st.cuda_stream)
+        buf = torch.full((want.total + G.BUF_SLACK,), G.CANARY_BUF, dtype=torch.uint8, device=dev)
+        du = torch.full((case.pool_bytes(case.d),), G.CANARY_POOL, dtype=torch.uint8, device=dev)
+        dc = torch.full((case.pool_bytes(case.d),), G.CANARY_POOL, dtype=torch.uint8, device=dev)
+        for l in reversed(range(case.num_layers)):          # order of the triggers does not matter
+            kvx.kvx_pack_layers(plan, l, l + 1, src_t.data_ptr(), buf.data_ptr(), want.total, st.cuda_stream)
+        for l in range(case.num_layers):
+            kvx.kvx_unpack_layers(plan, l, l + 1, buf.data_ptr(), want.total, du.data_ptr(), st.cuda_stream)
+            kvx.kvx_convert_layers(plan, l, l + 1, src_t.data_ptr(), dc.data_ptr(), st.cuda_stream)
+    st.synchronize()
+    got = G.Result(want.total, buf.cpu().numpy(), du.cpu().numpy(), dc.cpu().numpy())
+    G.assert_same(got, want, "layer by layer")
+    plan.destroy()
