@@ -225,6 +225,16 @@ kvx_status kvx_unpack_layers(const kvx_plan_t *plan, uint32_t layer_begin, uint3
 kvx_status kvx_convert_layers(const kvx_plan_t *plan, uint32_t layer_begin, uint32_t layer_end,
                               const void *src_pool, void *dst_pool, void *stream);
 
+/* Reference point, not the product path: the block-fixed transfer that section
+ * 2.2.3 ("Unnecessary Controls") argues against, in one-GPU form.  Produces the
+ * same buffer as kvx_pack, but moves the sender's blocks one after another, one
+ * device copy per (request, layer, K|V, page), issued from the host; with
+ * confirm_every = k > 0 the host also waits for the stream after every k
+ * blocks, standing in for the per-block confirmation between sender and
+ * receiver (k = 1: every block confirmed).  Needs no device workspace. */
+kvx_status kvx_pack_blockwise(const kvx_plan_t *plan, const void *src_pool, void *buf, uint64_t buf_bytes,
+                              uint32_t confirm_every, void *stream);
+
 /* Yardstick, not part of the transfer: a plain contiguous device-to-device copy
  * of `bytes` bytes (a multiple of 16; both pointers [device], 16-byte aligned,
  * not overlapping) made of the same 16-byte loads and stores as the data

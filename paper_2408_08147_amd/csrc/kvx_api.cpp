@@ -284,6 +284,7 @@ struct kvx_plan_s {
     uint64_t total = 0;
     std::vector<uint32_t> seq_lens;
     std::vector<uint64_t> token_prefix; // T_r, host copy for segment queries
+    std::vector<uint32_t> ids_s;        // sender's used page ids, request by request (for the block-by-block baseline)
     Sizing z;
     char *ws = nullptr; // device workspace (caller's), nullptr for a host-only plan
     PinnedBlock staging;
@@ -366,7 +367,8 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
 
     const kvx_batch_desc *b = sb ? sb : db;
     const uint32_t R = b->num_requests;
-    std::vector<uint32_t> ids_s, ids_d;
+    std::vector<uint32_t> &ids_s = p->ids_s;
+    std::vector<uint32_t> ids_d;
     if (s && (st = check_tables(p->s, sb, false, &ids_s, &p->s.used_pages)) != KVX_OK) { delete p; return st; }
     if (d && (st = check_tables(p->d, db, true, &ids_d, &p->d.used_pages)) != KVX_OK) { delete p; return st; }
 
@@ -632,6 +634,44 @@ kvx_status kvx_convert_layers(const kvx_plan_t *plan, uint32_t layer_begin, uint
                               const void *src_pool, void *dst_pool, void *stream) {
     if (!plan) return KVX_ERR_INVALID_ARG;
     return run_op(plan, OP_CONVERT, layer_begin, layer_end, src_pool, dst_pool, stream);
+}
+
+kvx_status kvx_pack_blockwise(const kvx_plan_t *plan, const void *src_pool, void *buf, uint64_t buf_bytes,
+                              uint32_t confirm_every, void *stream) {
+    if (!plan || !plan->s.present) return KVX_ERR_INVALID_ARG;
+    if (buf_bytes < plan->total) return KVX_ERR_CAPACITY;
+    if (plan->total == 0) return KVX_OK;
+    if (!src_pool || !buf) return KVX_ERR_INVALID_ARG;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const char *src = static_cast<const char *>(src_pool);
+    char *dst = static_cast<char *>(buf);
+    const Geometry &g = plan->s;
+    const uint32_t P = g.desc.page_tokens;
+    const uint64_t row = plan->row;
+    uint64_t first_id = 0, issued = 0;
+    for (uint32_t r = 0; r < plan->R; ++r) {
+        const uint64_t n = plan->seq_lens[r];
+        const uint64_t pages = (n + P - 1) / P;
+        for (uint32_t l = plan->l0; l < plan->l1; ++l)
+            for (uint32_t kv = 0; kv < 2; ++kv)
+                for (uint64_t j = 0; j < pages; ++j) {
+                    const uint64_t tokens = std::min<uint64_t>(P, n - j * P);
+                    const uint64_t so = l * g.sl + kv * g.sk + (uint64_t)plan->ids_s[first_id + j] * g.sp;
+                    const uint64_t bo = plan->token_prefix[r] * plan->bpt +
+                                        (((uint64_t)(l - plan->l0) * 2 + kv) * n + j * P) * row;
+                    hipError_t e;
+                    if (g.st == row) { // a page's tokens are contiguous: the block moves as one copy
+                        e = hipMemcpyAsync(dst + bo, src + so, tokens * row, hipMemcpyDeviceToDevice, hs);
+                    } else {
+                        e = hipMemcpy2DAsync(dst + bo, row, src + so, g.st, row, tokens, hipMemcpyDeviceToDevice, hs);
+                    }
+                    if (e != hipSuccess) return KVX_ERR_DEVICE;
+                    if (confirm_every && ++issued % confirm_every == 0 && hipStreamSynchronize(hs) != hipSuccess)
+                        return KVX_ERR_DEVICE;
+                }
+        first_id += pages;
+    }
+    return KVX_OK;
 }
 
 kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const kvx_launch_cfg *cfg,

@@ -23,7 +23,7 @@ EXPORTS = (
     "kvx_plan_workspace_bytes", "kvx_plan", "kvx_plan_destroy", "kvx_plan_total_bytes",
     "kvx_plan_segment", "kvx_plan_request_segment", "kvx_plan_get_tables", "kvx_plan_set_launch",
     "kvx_plan_get_launch", "kvx_pack", "kvx_unpack", "kvx_convert", "kvx_pack_layers",
-    "kvx_unpack_layers", "kvx_convert_layers", "kvx_copy_yardstick",
+    "kvx_unpack_layers", "kvx_convert_layers", "kvx_pack_blockwise", "kvx_copy_yardstick",
     "kvx_status_string",
 )
 
@@ -127,6 +127,7 @@ def load():
     lib.kvx_unpack_layers.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_uint64, C.c_void_p,
                                       C.c_void_p]
     lib.kvx_convert_layers.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.kvx_pack_blockwise.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p]
     lib.kvx_copy_yardstick.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(LaunchCfg), C.c_void_p]
     for name in EXPORTS:
         if name not in ("kvx_status_string", "kvx_plan_destroy"):
@@ -264,6 +265,13 @@ def kvx_convert_layers(plan: Plan, layer_begin: int, layer_end: int, src_pool: i
     _check(load().kvx_convert_layers(plan.handle, layer_begin, layer_end, C.c_void_p(src_pool or None),
                                      C.c_void_p(dst_pool or None), C.c_void_p(stream or None)),
            "kvx_convert_layers")
+
+
+def kvx_pack_blockwise(plan: Plan, src_pool: int, buf: int, buf_bytes: int, confirm_every: int = 0,
+                       stream: int = 0) -> None:
+    _check(load().kvx_pack_blockwise(plan.handle, C.c_void_p(src_pool or None), C.c_void_p(buf or None),
+                                     buf_bytes, confirm_every, C.c_void_p(stream or None)),
+           "kvx_pack_blockwise")
 
 
 def kvx_copy_yardstick(dst: int, src: int, nbytes: int, stream: int = 0, unroll: int = 0,

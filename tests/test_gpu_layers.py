@@ -107,3 +107,54 @@ def test_all_layers_one_by_one_equal_the_whole():
     got = G.Result(want.total, buf.cpu().numpy(), du.cpu().numpy(), dc.cpu().numpy())
     G.assert_same(got, want, "layer by layer")
     plan.destroy()
+
+
+@pytest.mark.parametrize("confirm_every", [0, 1, 7])
+def test_blockwise_baseline_gives_the_same_buffer(confirm_every):
+    """The block-by-block reference point must produce kvx_pack's bytes."""
+    import torch
+    case, src = setup_case(0, 0, 16, 16)
+    want = G.run_oracle(case, src, 1, 4)
+    dev = torch.device("cuda:0")
+    st = torch.cuda.Stream(device=dev)
+    sp = case.kvx_pool(case.s)
+    sb = kvx.BatchDesc(case.seq_lens, case.ids_s, case.offs_s)
+    plan = kvx.kvx_plan(sp, sb, None, None, 1, 4)            # host-only plan: no workspace needed
+    with torch.cuda.stream(st):
+        src_t = torch.from_numpy(src).to(dev)
+        buf = torch.full((want.total + G.BUF_SLACK,), G.CANARY_BUF, dtype=torch.uint8, device=dev)
+    st.synchronize()
+    kvx.kvx_pack_blockwise(plan, src_t.data_ptr(), buf.data_ptr(), want.total, confirm_every, st.cuda_stream)
+    st.synchronize()
+    assert np.array_equal(buf.cpu().numpy(), want.buf)
+    plan.destroy()
+
+
+def test_blockwise_baseline_with_padded_rows():
+    import torch
+    rng = np.random.default_rng(77)
+    L, H, D, e, Ps = 2, 2, 32, 2, 8
+    row = H * D * e
+    lens = np.array([9, 0, 40, 8], dtype=np.uint32)
+    nps = 24
+    st_tok = row + 32
+    st_page = Ps * st_tok + 64
+    st_kv = nps * st_page
+    st_layer = 2 * st_kv + 256
+    s = G.Side(Ps, nps, 0, (st_layer, st_kv, st_page, st_tok), L * st_layer)
+    ids, offs = G.tables(rng, lens, Ps, nps)
+    case = G.Case(L, H, D, e, lens, s, s, ids, offs, ids, offs)
+    src = rng.integers(0, 256, size=case.pool_bytes(s), dtype=np.uint8)
+    po, bo = case.oracle_pool(s), kvxo.Batch(lens, ids, offs)
+    total = kvxo.total_bytes(po, bo, 0, L)
+    want = np.full(total + 64, 0x5A, dtype=np.uint8)
+    kvxo.pack(po, bo, 0, L, src, want)
+    dev = torch.device("cuda:0")
+    plan = kvx.kvx_plan(case.kvx_pool(s), kvx.BatchDesc(lens, ids, offs), None, None, 0, L)
+    src_t = torch.from_numpy(src).to(dev)
+    buf = torch.full((total + 64,), 0x5A, dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    kvx.kvx_pack_blockwise(plan, src_t.data_ptr(), buf.data_ptr(), total, 0, 0)
+    torch.cuda.synchronize()
+    assert np.array_equal(buf.cpu().numpy(), want)
+    plan.destroy()
