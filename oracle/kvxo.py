@@ -20,7 +20,7 @@ _lib = None
 class _Pool(C.Structure):
     _fields_ = [("num_layers", C.c_uint32), ("num_kv_heads", C.c_uint32), ("head_dim", C.c_uint32),
                 ("elem_bytes", C.c_uint32), ("page_tokens", C.c_uint32), ("num_pages", C.c_uint32),
-                ("layout", C.c_uint32), ("reserved", C.c_uint32),
+                ("layout", C.c_uint32), ("inner", C.c_uint32),
                 ("stride_layer", C.c_uint64), ("stride_kv", C.c_uint64),
                 ("stride_page", C.c_uint64), ("stride_token", C.c_uint64)]
 
@@ -55,10 +55,12 @@ class Pool:
     stride_kv: int = 0
     stride_page: int = 0
     stride_token: int = 0
+    inner: int = 0          # arrangement inside a page: 0 [token][head][dim], 1 [head][token][dim],
+                            # 2 [head][dim/x][token][x] with x = 16/elem_bytes
 
     def c(self) -> _Pool:
         return _Pool(self.num_layers, self.num_kv_heads, self.head_dim, self.elem_bytes,
-                     self.page_tokens, self.num_pages, self.layout, 0,
+                     self.page_tokens, self.num_pages, self.layout, self.inner,
                      self.stride_layer, self.stride_kv, self.stride_page, self.stride_token)
 
     @property

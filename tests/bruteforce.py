@@ -19,26 +19,40 @@ def table(ids, offs, r):
     return [int(x) for x in ids[int(offs[r]):int(offs[r + 1])]]
 
 
-def flat_to_dict(flat: np.ndarray, L, NP, P, row, layout):
+def _page_view(flat: np.ndarray, L, NP, P, row, layout, inner, heads):
+    """The pool as an N-d array whose leading axes are (layer, kv, page) and
+    whose page-internal axes are spelled as the arrangement's name says; the
+    returned function picks one token row out of it as [head][dim] bytes."""
+    lead = (L, 2, NP) if layout == LAYER_MAJOR else (NP, L, 2)
+    hb = row // heads                                   # bytes of one head of one token
+    if inner == 0:                                      # [token][head][dim]
+        a = flat.reshape(*lead, P, row)
+        pick = lambda pg, s: pg[s]
+    elif inner == 1:                                    # [head][token][dim]
+        a = flat.reshape(*lead, heads, P, hb)
+        pick = lambda pg, s: pg[:, s, :]
+    else:                                               # [head][dim/x][token][x], x elements = 16 bytes
+        a = flat.reshape(*lead, heads, hb // 16, P, 16)
+        pick = lambda pg, s: pg[:, :, s, :]
     if layout == LAYER_MAJOR:
-        a = flat.reshape(L, 2, NP, P, row)
-        get = lambda l, c, p, s: a[l, c, p, s]
+        page = lambda l, c, p: a[l, c, p]
     else:
-        a = flat.reshape(NP, L, 2, P, row)
-        get = lambda l, c, p, s: a[p, l, c, s]
-    return {(l, c, p, s): bytes(get(l, c, p, s))
+        page = lambda l, c, p: a[p, l, c]
+    return a, page, pick
+
+
+def flat_to_dict(flat: np.ndarray, L, NP, P, row, layout, inner=0, heads=1):
+    _, page, pick = _page_view(flat, L, NP, P, row, layout, inner, heads)
+    return {(l, c, p, s): bytes(np.ascontiguousarray(pick(page(l, c, p), s)).reshape(-1))
             for l in range(L) for c in range(2) for p in range(NP) for s in range(P)}
 
 
-def dict_to_flat(d: dict, L, NP, P, row, layout) -> np.ndarray:
-    if layout == LAYER_MAJOR:
-        a = np.zeros((L, 2, NP, P, row), dtype=np.uint8)
-        for (l, c, p, s), v in d.items():
-            a[l, c, p, s] = np.frombuffer(v, dtype=np.uint8)
-    else:
-        a = np.zeros((NP, L, 2, P, row), dtype=np.uint8)
-        for (l, c, p, s), v in d.items():
-            a[p, l, c, s] = np.frombuffer(v, dtype=np.uint8)
+def dict_to_flat(d: dict, L, NP, P, row, layout, inner=0, heads=1) -> np.ndarray:
+    flat = np.zeros(L * 2 * NP * P * row, dtype=np.uint8)
+    a, page, pick = _page_view(flat, L, NP, P, row, layout, inner, heads)
+    for (l, c, p, s), v in d.items():
+        tgt = pick(page(l, c, p), s)
+        tgt[...] = np.frombuffer(v, dtype=np.uint8).reshape(tgt.shape)
     return a.reshape(-1)
 
 

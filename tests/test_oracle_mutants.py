@@ -30,8 +30,16 @@ MUTANTS = {
                                    "uint32_t page = (uint32_t)logical;"),
     "csr_offset_ignored": ("uint32_t page = b->block_ids[b->block_offsets[r] + logical];",
                            "uint32_t page = b->block_ids[logical];"),
-    "convert_uses_sender_table_twice": ("if (pool_addr(pd, bd, (uint32_t)r, l, c, t, &d))",
-                                        "if (pool_addr(pd, bs, (uint32_t)r, l, c, t, &d))"),
+    "convert_uses_sender_table_twice": ("if (pool_place(pd, bd, (uint32_t)r, l, c, t, &to))",
+                                        "if (pool_place(pd, bs, (uint32_t)r, l, c, t, &to))"),
+    "head_major_forgets_slot": ("return w->base + (h * P + w->slot) * D * e + d * e;",
+                                "return w->base + (h * P) * D * e + d * e;"),
+    "head_major_is_token_major": ("return w->base + (h * P + w->slot) * D * e + d * e;",
+                                  "return w->base + (w->slot * g->num_kv_heads + h) * D * e + d * e;"),
+    "split_groups_not_16_bytes": ("uint64_t x = 16 / e;", "uint64_t x = 8 / e ? 8 / e : 1;"),
+    "split_token_outside_group": ("return w->base + ((h * (D / x) + d / x) * P + w->slot) * 16 + (d % x) * e;",
+                                  "return w->base + ((h * P + w->slot) * (D / x) + d / x) * 16 + (d % x) * e;"),
+    "split_lane_order_reversed": ("+ (d % x) * e;", "+ (x - 1 - d % x) * e;"),
     "segment_length_half": ("*len = 2 * (uint64_t)b->seq_lens[r] * row_bytes(p);",
                             "*len = (uint64_t)b->seq_lens[r] * row_bytes(p);"),
     "total_forgets_kv_factor": ("* 2\n                 * tokens_before(b, b->num_requests);",
@@ -40,15 +48,10 @@ MUTANTS = {
                                "return (uint64_t)p->num_kv_heads * p->head_dim;"),
 }
 MUTANTS["unpack_writes_one_row_past_length"] = (
-    "for (uint32_t t = 0; t < b->seq_lens[r]; ++t) {\n"
-    "                    uint64_t a;\n"
-    "                    if (pool_addr(p, b, (uint32_t)r, l, c, t, &a)) { bad = 1; continue; }\n"
-    "                    memcpy(pool + a, buf",
-    "for (uint32_t t = 0; t < b->seq_lens[r]; ++t) {\n"
-    "                    uint64_t a;\n"
-    "                    if (pool_addr(p, b, (uint32_t)r, l, c, t, &a)) { bad = 1; continue; }\n"
-    "                    if (t + 1 == b->seq_lens[r] && (t + 1) % p->page_tokens) memcpy(pool + a + row, buf, row);\n"
-    "                    memcpy(pool + a, buf")
+    "                    copy_token(p, pool, &to, buf, &from);",
+    "                    copy_token(p, pool, &to, buf, &from);\n"
+    "                    if (t + 1 == b->seq_lens[r] && (t + 1) % p->page_tokens) {\n"
+    "                        to.slot += 1; copy_token(p, pool, &to, buf, &from); }")
 
 
 def _run_pins():
@@ -62,6 +65,8 @@ def _run_pins():
                             pins.test_roundtrip_stamps_and_canaries(pins.PM, pins.LM, 16, 128),
                             pins.test_roundtrip_stamps_and_canaries(pins.LM, pins.LM, 5, 7)]),
         ("take", lambda: pins.test_pack_reduces_to_numpy_take(0)),
+        ("inner_bruteforce", lambda: [pins.test_bruteforce_tiny(*c) for c in pins.INNER[::7]]),
+        ("inner_transposes", lambda: pins.test_inner_arrangements_reduce_to_transposes(2, 16)),
         ("transpose", pins.test_convert_reduces_to_transpose),
         ("algebra", pins.test_convert_equals_unpack_of_pack),
         ("ranges", pins.test_whole_range_is_per_layer_ranges_at_segment_offsets),

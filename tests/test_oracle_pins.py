@@ -55,22 +55,36 @@ for L, H, D, e in [(1, 1, 3, 1), (2, 2, 4, 2), (2, 1, 8, 1)]:
             TINY.append((L, H, D, e, Ps, Pd, ls, ld))
 
 
+# page-internal arrangements (0 rows, 1 head-major, 2 token axis inside 16-byte dim groups) on either side
+INNER = []
+for H, D, e in [(2, 16, 1), (3, 8, 2), (1, 8, 4)]:
+    for Ps, Pd in [(4, 4), (2, 3), (4, 1), (3, 8)]:
+        for (ls, ins), (ld, ind) in [((LM, 1), (LM, 0)), ((LM, 0), (PM, 2)), ((PM, 2), (LM, 1)),
+                                      ((PM, 1), (PM, 1)), ((LM, 2), (LM, 2)), ((LM, 0), (LM, 1))]:
+            INNER.append((2, H, D, e, Ps, Pd, ls, ld, ins, ind))
+
+
+@pytest.mark.parametrize("L,H,D,e,Ps,Pd,ls,ld,ins,ind", INNER)
+def test_bruteforce_tiny_inner_arrangements(L, H, D, e, Ps, Pd, ls, ld, ins, ind):
+    test_bruteforce_tiny(L, H, D, e, Ps, Pd, ls, ld, ins, ind)
+
+
 @pytest.mark.parametrize("L,H,D,e,Ps,Pd,ls,ld", TINY)
-def test_bruteforce_tiny(L, H, D, e, Ps, Pd, ls, ld):
-    rng = np.random.default_rng(hash((L, H, D, e, Ps, Pd, ls, ld)) & 0xFFFFFFFF)
+def test_bruteforce_tiny(L, H, D, e, Ps, Pd, ls, ld, ins=0, ind=0):
+    rng = np.random.default_rng(hash((L, H, D, e, Ps, Pd, ls, ld, ins, ind)) & 0xFFFFFFFF)
     P = max(Ps, Pd)
     lens = np.array([0, 1, P - 1, P, P + 1, 2 * P, 2 * P + 1, int(rng.integers(0, 5 * P))],
                     dtype=np.uint32)
     rng.shuffle(lens)
     row = H * D * e
     NPs, NPd = 40, 64
-    ps = kvxo.Pool(L, H, D, e, Ps, NPs, ls)
-    pd = kvxo.Pool(L, H, D, e, Pd, NPd, ld)
+    ps = kvxo.Pool(L, H, D, e, Ps, NPs, ls, inner=ins)
+    pd = kvxo.Pool(L, H, D, e, Pd, NPd, ld, inner=ind)
     ids_s, offs_s = make_tables(rng, lens, Ps, NPs, unique=False, extra=1)   # shared source pages allowed
     ids_d, offs_d = make_tables(rng, lens, Pd, NPd, unique=True, extra=1)
     bs, bd = kvxo.Batch(lens, ids_s, offs_s), kvxo.Batch(lens, ids_d, offs_d)
     src = rand_pool(rng, ps)
-    src_d = bf.flat_to_dict(src, L, NPs, Ps, row, ls)
+    src_d = bf.flat_to_dict(src, L, NPs, Ps, row, ls, ins, H)
 
     for l0, l1 in [(0, L), (L - 1, L), (0, 0)]:
         want = bf.pack(src_d, Ps, lens, ids_s, offs_s, l0, l1)
@@ -83,15 +97,15 @@ def test_bruteforce_tiny(L, H, D, e, Ps, Pd, ls, ld):
         canary = rng.integers(0, 256, size=pd.nbytes, dtype=np.uint8)
         dst = canary.copy()
         kvxo.unpack(pd, bd, l0, l1, buf, dst)
-        dst_d = bf.flat_to_dict(canary, L, NPd, Pd, row, ld)
+        dst_d = bf.flat_to_dict(canary, L, NPd, Pd, row, ld, ind, H)
         bf.unpack(want, row, dst_d, Pd, lens, ids_d, offs_d, l0, l1)
-        assert np.array_equal(dst, bf.dict_to_flat(dst_d, L, NPd, Pd, row, ld))
+        assert np.array_equal(dst, bf.dict_to_flat(dst_d, L, NPd, Pd, row, ld, ind, H))
 
         dst2 = canary.copy()
         kvxo.convert(ps, bs, pd, bd, l0, l1, src, dst2)
-        dst2_d = bf.flat_to_dict(canary, L, NPd, Pd, row, ld)
+        dst2_d = bf.flat_to_dict(canary, L, NPd, Pd, row, ld, ind, H)
         bf.convert(src_d, Ps, ids_s, offs_s, dst2_d, Pd, ids_d, offs_d, lens, l0, l1)
-        assert np.array_equal(dst2, bf.dict_to_flat(dst2_d, L, NPd, Pd, row, ld))
+        assert np.array_equal(dst2, bf.dict_to_flat(dst2_d, L, NPd, Pd, row, ld, ind, H))
 
 
 # ---------------------------------------------------------------- 3. closed form + paper numbers
@@ -241,6 +255,40 @@ def test_convert_reduces_to_transpose():
     back = np.zeros(ps.nbytes, dtype=np.uint8)
     kvxo.convert(pd, b, ps, b, 0, L, dst, back)
     assert np.array_equal(back, src)
+
+
+@pytest.mark.parametrize("e,D", [(2, 16), (1, 32), (4, 8)])
+def test_inner_arrangements_reduce_to_transposes(e, D):
+    """Identity block tables, full pages: converting between page-internal
+    arrangements is a plain axis permutation of the page."""
+    rng = np.random.default_rng(8 + e)
+    L, H, P, NP = 2, 3, 4, 5
+    x = 16 // e
+    rows = kvxo.Pool(L, H, D, e, P, NP, LM, inner=0)
+    heads = kvxo.Pool(L, H, D, e, P, NP, LM, inner=1)
+    split = kvxo.Pool(L, H, D, e, P, NP, LM, inner=2)
+    src = rand_pool(rng, rows)
+    b = kvxo.Batch([NP * P], np.arange(NP, dtype=np.uint32), [0, NP])
+    as_elems = src.reshape(L, 2, NP, P, H, D // x, x * e)           # [token][head][dim/x][x]
+    out = np.zeros(rows.nbytes, dtype=np.uint8)
+    kvxo.convert(rows, b, heads, b, 0, L, src, out)
+    assert np.array_equal(out, np.ascontiguousarray(as_elems.transpose(0, 1, 2, 4, 3, 5, 6)).reshape(-1))
+    kvxo.convert(rows, b, split, b, 0, L, src, out)
+    want_split = np.ascontiguousarray(as_elems.transpose(0, 1, 2, 4, 5, 3, 6)).reshape(-1)
+    assert np.array_equal(out, want_split)
+    back = np.zeros(rows.nbytes, dtype=np.uint8)
+    kvxo.convert(split, b, rows, b, 0, L, want_split, back)
+    assert np.array_equal(back, src)
+    # pack out of either arrangement gives the same buffer as out of rows
+    bufs = []
+    for pool, data in ((rows, src), (split, want_split)):
+        buf = np.zeros(kvxo.total_bytes(pool, b, 0, L), dtype=np.uint8)
+        kvxo.pack(pool, b, 0, L, data, buf)
+        bufs.append(buf)
+    assert np.array_equal(bufs[0], bufs[1])
+    with pytest.raises(ValueError):                                  # 16-byte groups need head_dim*e % 16 == 0
+        kvxo.pack(kvxo.Pool(1, 1, 4, 2, 4, 2, LM, inner=2), kvxo.Batch([1], [0], [0, 1]), 0, 1,
+                  np.zeros(64, np.uint8), np.zeros(64, np.uint8))
 
 
 def test_explicit_strides_match_padded_numpy_view():
