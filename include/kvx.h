@@ -30,7 +30,10 @@
  *     and every base pointer must be a multiple of 16 bytes.
  *   - A pool addresses a row as
  *         layer*stride_layer + kv*stride_kv + page*stride_page + slot*stride_token
- *     with kv = 0 for K, 1 for V.
+ *     with kv = 0 for K, 1 for V.  (Pools whose pages are not [token][head][dim]
+ *     inside, see kvx_inner, address 16-byte units instead of rows; they are
+ *     moved by a kernel that stages tiles through LDS where the two sides
+ *     disagree on which axis is contiguous.)
  *   - The buffer of a plan over layers [l0,l1) holds the requests in batch order
  *     with no padding; inside a request the layers ascend, each layer is all K
  *     rows then all V rows, tokens ascending ("one after another").  With
@@ -62,9 +65,20 @@ typedef enum {
 } kvx_status;
 
 typedef enum {
-    KVX_LAYOUT_LAYER_MAJOR = 0, /* [layer][K,V][page][token][head][dim] */
-    KVX_LAYOUT_PAGE_MAJOR = 1   /* [page][layer][K,V][token][head][dim] */
+    KVX_LAYOUT_LAYER_MAJOR = 0, /* [layer][K,V][page]{page} */
+    KVX_LAYOUT_PAGE_MAJOR = 1   /* [page][layer][K,V]{page} */
 } kvx_layout;
+
+/* Arrangement of the page_tokens tokens inside one {page} (one layer, K or V).
+ * The receiver restores "desired discrete blocks" (sections 1 and 2.2.3); the
+ * paper fixes no block-internal layout, so three are offered.  The contiguous
+ * buffer is always [token][head][dim]. */
+typedef enum {
+    KVX_INNER_TOKEN_ROWS = 0,      /* [token][head][dim]: a token row is contiguous */
+    KVX_INNER_HEAD_MAJOR = 1,      /* [head][token][dim] */
+    KVX_INNER_DIM_SPLIT_TOKEN = 2  /* [head][dim/x][token][x], x = 16/elem_bytes elements: the token axis sits
+                                      inside every 16-byte group of the head dimension */
+} kvx_inner;
 
 /* Geometry of one paged pool (section 2.2.3, "Block-fixed Management": device
  * memory organised as discrete blocks of fixed size).  The base pointer is
@@ -79,7 +93,9 @@ typedef struct {
     uint32_t page_tokens;  /* tokens per page (block) */
     uint32_t num_pages;    /* pages in the pool */
     uint32_t layout;       /* kvx_layout */
-    uint32_t reserved;     /* must be 0 */
+    uint32_t inner;        /* kvx_inner; anything but TOKEN_ROWS needs the derived (all-zero) strides,
+                              head_dim*elem_bytes a multiple of 16, and for DIM_SPLIT_TOKEN elem_bytes
+                              dividing 16 */
     uint64_t stride_layer, stride_kv, stride_page, stride_token;
 } kvx_pool_desc;
 
@@ -231,7 +247,8 @@ kvx_status kvx_convert_layers(const kvx_plan_t *plan, uint32_t layer_begin, uint
  * device copy per (request, layer, K|V, page), issued from the host; with
  * confirm_every = k > 0 the host also waits for the stream after every k
  * blocks, standing in for the per-block confirmation between sender and
- * receiver (k = 1: every block confirmed).  Needs no device workspace. */
+ * receiver (k = 1: every block confirmed).  Needs no device workspace.  Only for
+ * sender pools with [token][head][dim] pages (else KVX_ERR_UNSUPPORTED). */
 kvx_status kvx_pack_blockwise(const kvx_plan_t *plan, const void *src_pool, void *buf, uint64_t buf_bytes,
                               uint32_t confirm_every, void *stream);
 

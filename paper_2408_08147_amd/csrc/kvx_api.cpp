@@ -23,7 +23,11 @@ struct Geometry {
     uint64_t row = 0;
     uint64_t sl = 0, sk = 0, sp = 0, st = 0; // resolved byte strides
     bool custom_strides = false;
-    uint32_t quantum = 0;                    // tokens contiguous inside a page
+    uint32_t quantum = 0;                    // tokens that form one affine span inside a page
+    // 16-byte unit u of the token in slot s sits at s*token_step + (u/upg)*granule_step + (u%upg)*16
+    uint64_t token_step = 0, granule_step = 0;
+    uint32_t upg = 0;
+    bool token_fast = false;                 // consecutive tokens are nearer than consecutive units
     uint64_t used_pages = 0;                 // sum over requests of ceil(n/P)
 };
 
@@ -77,7 +81,7 @@ void pinned_release(PinnedBlock b) {
 
 kvx_status resolve_pool(const kvx_pool_desc *d, Geometry *g) {
     if (!d->num_layers || !d->num_kv_heads || !d->head_dim || !d->elem_bytes || !d->page_tokens ||
-        !d->num_pages || d->reserved)
+        !d->num_pages || d->inner > KVX_INNER_DIM_SPLIT_TOKEN)
         return KVX_ERR_INVALID_ARG;
     g->present = true;
     g->desc = *d;
@@ -86,6 +90,13 @@ kvx_status resolve_pool(const kvx_pool_desc *d, Geometry *g) {
     if (row * d->page_tokens >= (1ull << 32)) return KVX_ERR_UNSUPPORTED;
     g->row = row;
     const bool any = d->stride_layer || d->stride_kv || d->stride_page || d->stride_token;
+    if (d->inner != KVX_INNER_TOKEN_ROWS) {
+        const uint64_t head_bytes = (uint64_t)d->head_dim * d->elem_bytes;
+        if (any) return KVX_ERR_INVALID_ARG;
+        if (head_bytes % 16) return KVX_ERR_ALIGNMENT;
+        if (d->inner == KVX_INNER_DIM_SPLIT_TOKEN && 16 % d->elem_bytes) return KVX_ERR_INVALID_ARG;
+        if (row / 16 >= 65536) return KVX_ERR_UNSUPPORTED;
+    }
     if (any) {
         if (!d->stride_layer || !d->stride_kv || !d->stride_page || !d->stride_token)
             return KVX_ERR_INVALID_ARG;
@@ -111,6 +122,19 @@ kvx_status resolve_pool(const kvx_pool_desc *d, Geometry *g) {
         return KVX_ERR_INVALID_ARG;
     }
     g->quantum = (g->st == row) ? d->page_tokens : 1u;
+    g->token_step = g->st;
+    g->upg = (uint32_t)(row / 16);
+    if (d->inner == KVX_INNER_HEAD_MAJOR) {
+        const uint64_t head_bytes = (uint64_t)d->head_dim * d->elem_bytes;
+        g->token_step = head_bytes;
+        g->upg = (uint32_t)(head_bytes / 16);
+        g->granule_step = head_bytes * d->page_tokens;
+    } else if (d->inner == KVX_INNER_DIM_SPLIT_TOKEN) {
+        g->token_step = 16;
+        g->upg = 1;
+        g->granule_step = 16ull * d->page_tokens;
+        g->token_fast = true;
+    }
     return KVX_OK;
 }
 
@@ -432,7 +456,7 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
             src_side.ids = reinterpret_cast<const uint32_t *>(p->ws + z.off_ids_s);
             src_side.page_prefix = sp.prefix[SCAN_PAGES_S];
             src_side.stride_page = p->s.sp;
-            src_side.stride_token = p->s.st;
+            src_side.stride_token = p->s.token_step;
             src_side.page_tokens = s->page_tokens;
             src_side.quantum = p->s.quantum;
         }
@@ -440,7 +464,7 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
             dst_side.ids = reinterpret_cast<const uint32_t *>(p->ws + z.off_ids_d);
             dst_side.page_prefix = sp.prefix[SCAN_PAGES_D];
             dst_side.stride_page = p->d.sp;
-            dst_side.stride_token = p->d.st;
+            dst_side.stride_token = p->d.token_step;
             dst_side.page_tokens = d->page_tokens;
             dst_side.quantum = p->d.quantum;
         }
@@ -539,6 +563,65 @@ kvx_status kvx_plan_get_launch(const kvx_plan_t *plan, kvx_launch_cfg *out) {
 
 namespace {
 
+XposeSide xpose_side(const Geometry &g, bool is_buf, uint64_t row) {
+    XposeSide x{};
+    x.is_buf = is_buf;
+    if (is_buf) { // the buffer: plain [token][head][dim] rows
+        x.token_step = row;
+        x.units_per_granule = (uint32_t)(row / 16);
+    } else {
+        x.stride_layer = g.sl;
+        x.stride_kv = g.sk;
+        x.token_step = g.token_step;
+        x.granule_step = g.granule_step;
+        x.units_per_granule = g.upg;
+    }
+    x.granule_magic = x.units_per_granule > 1 ? (uint32_t)((1ull << 32) / x.units_per_granule) + 1u : 0u;
+    return x;
+}
+
+// The same as run_op's launch, for pools whose pages are not [token][head][dim] inside.
+kvx_status run_xpose(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, const void *src, void *dst,
+                     void *stream) {
+    const OpShape &o = plan->z.ops[op];
+    const kvx_launch_cfg &c = plan->launch;
+    XposeParams xp{};
+    xp.runs = reinterpret_cast<const kvx_run *>(plan->ws + plan->z.off_runs[op]);
+    xp.src = static_cast<const char *>(src);
+    xp.dst = static_cast<char *>(dst);
+    xp.s = xpose_side(plan->s, op == OP_UNPACK, plan->row);
+    xp.d = xpose_side(plan->d, op == OP_PACK, plan->row);
+    const bool src_tf = op != OP_UNPACK && plan->s.token_fast;
+    const bool dst_tf = op != OP_PACK && plan->d.token_fast;
+    xp.row = (uint32_t)plan->row;
+    xp.units_per_row = (uint32_t)(plan->row / 16);
+    xp.layer_begin = plan->l0;
+    xp.lc_first = 2 * (lb - plan->l0);
+    xp.num_lc = 2 * (le - lb);
+    xp.num_runs = (uint32_t)o.num_runs;
+    // 1024 units per tile: as wide along the row as the row allows (up to 64 units = 1 KiB), the rest in tokens
+    xp.log2_uu = xp.units_per_row >= 64 ? 6 : (xp.units_per_row >= 32 ? 5 : 4);
+    xp.log2_tt = 10 - xp.log2_uu;
+    const uint32_t max_tokens = o.max_run_bytes / xp.row;
+    xp.tiles_t = (max_tokens + (1u << xp.log2_tt) - 1) >> xp.log2_tt;
+    xp.tiles_u = (xp.units_per_row + (1u << xp.log2_uu) - 1) >> xp.log2_uu;
+    const uint64_t total = (uint64_t)xp.num_lc * xp.num_runs * xp.tiles_t * xp.tiles_u;
+    if (total >= (1ull << 32)) return KVX_ERR_UNSUPPORTED;
+    xp.total_tiles = (uint32_t)total;
+    xp.order = c.order;
+    if (!xp.order)
+        xp.order = (op != OP_PACK && plan->d.desc.layout == KVX_LAYOUT_PAGE_MAJOR) ? 2 : 1;
+    xp.group = o.group_slots;
+    const uint32_t grid_cap = std::min<uint32_t>(c.max_workgroups, (1u << 31) / kXposeThreads - 8u);
+    uint32_t grid = std::min(xp.total_tiles, grid_cap);
+    if (c.xcd_swizzle == 2) {
+        grid = (grid + 7u) / 8u * 8u;
+        xp.swizzle_chunk = grid / 8u;
+    }
+    hipError_t e = launch_xpose(xp, src_tf, dst_tf, c.nontemporal == 2, grid, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? KVX_OK : KVX_ERR_DEVICE;
+}
+
 // Launches one operation over layers [lb, le) of the plan's range.  Buffer offsets stay those of the
 // plan's whole range, so a sub-range touches exactly its own segments of the same buffer.
 kvx_status run_op(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, const void *src, void *dst,
@@ -550,6 +633,9 @@ kvx_status run_op(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, const
     if (!src || !dst) return KVX_ERR_INVALID_ARG;
     if (((uintptr_t)src | (uintptr_t)dst) % 16) return KVX_ERR_ALIGNMENT;
     const kvx_launch_cfg &c = plan->launch;
+    const bool src_rows = (op == OP_UNPACK) || plan->s.desc.inner == KVX_INNER_TOKEN_ROWS;
+    const bool dst_rows = (op == OP_PACK) || plan->d.desc.inner == KVX_INNER_TOKEN_ROWS;
+    if (!src_rows || !dst_rows) return run_xpose(plan, op, lb, le, src, dst, stream);
     CopyParams cp{};
     cp.runs = reinterpret_cast<const kvx_run *>(plan->ws + plan->z.off_runs[op]);
     cp.src = static_cast<const char *>(src);
@@ -639,6 +725,7 @@ kvx_status kvx_convert_layers(const kvx_plan_t *plan, uint32_t layer_begin, uint
 kvx_status kvx_pack_blockwise(const kvx_plan_t *plan, const void *src_pool, void *buf, uint64_t buf_bytes,
                               uint32_t confirm_every, void *stream) {
     if (!plan || !plan->s.present) return KVX_ERR_INVALID_ARG;
+    if (plan->s.desc.inner != KVX_INNER_TOKEN_ROWS) return KVX_ERR_UNSUPPORTED; // blocks would not be contiguous
     if (buf_bytes < plan->total) return KVX_ERR_CAPACITY;
     if (plan->total == 0) return KVX_OK;
     if (!src_pool || !buf) return KVX_ERR_INVALID_ARG;

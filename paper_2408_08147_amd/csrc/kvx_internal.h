@@ -74,6 +74,41 @@ struct CopyParams {
     uint32_t swizzle_block;   // 0 = eighths of the grid, else tiles per block dealt round-robin to the XCDs
 };
 
+// One side of the tile-transposing kernel.  A row is row/16 units of 16 bytes; unit u of the token in
+// slot s of a page lives at  page_base + s*token_step + (u / units_per_granule)*granule_step
+// + (u % units_per_granule)*16.
+struct XposeSide {
+    uint64_t stride_layer, stride_kv; // pool side only
+    uint64_t token_step;
+    uint64_t granule_step;
+    uint32_t units_per_granule;
+    uint32_t granule_magic;           // floor(2^32 / units_per_granule) + 1; unused when units_per_granule == 1
+    uint32_t is_buf;
+    uint32_t pad;
+};
+
+struct XposeParams {
+    const kvx_run *runs;
+    const char *src;
+    char *dst;
+    XposeSide s, d;
+    uint32_t row;
+    uint32_t units_per_row;
+    uint32_t layer_begin, lc_first, num_lc;
+    uint32_t num_runs;
+    uint32_t log2_tt, log2_uu;        // tile = 2^log2_tt tokens x 2^log2_uu units = 1024 units
+    uint32_t tiles_t, tiles_u;        // tiles per run along tokens / along the row
+    uint32_t total_tiles;
+    uint32_t order, group;
+    uint32_t swizzle_chunk;
+};
+
+constexpr uint32_t kXposeThreads = 256;
+constexpr uint32_t kXposeCells = 1024; // 16-byte units per tile (16 KiB)
+
+hipError_t launch_xpose(const XposeParams &p, bool src_token_fast, bool dst_token_fast, bool nontemporal,
+                        uint32_t grid, hipStream_t stream);
+
 inline uint32_t tile_bytes(uint32_t threads, uint32_t unroll) { return threads * 16u * unroll; }
 inline bool valid_threads(uint32_t t) { return t == 64 || t == 128 || t == 256 || t == 512 || t == 1024; }
 inline bool valid_unroll(uint32_t u) { return u == 1 || u == 2 || u == 4 || u == 8; }

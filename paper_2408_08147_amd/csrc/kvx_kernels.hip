@@ -15,6 +15,10 @@
 //                and stores, all loads of a tile in flight before its first
 //                store.  No LDS: with token rows contiguous on both sides no
 //                byte changes its position inside a 16-byte unit.
+//   xpose_kernel the same three operations when a pool's pages are not
+//                [token][head][dim] inside: tiles of tokens x 16-byte units,
+//                staged through LDS when one side is contiguous along the row
+//                and the other along the tokens.
 #include <algorithm>
 
 #include "kvx_internal.h"
@@ -241,6 +245,105 @@ __global__ __launch_bounds__(T) void copy_kernel(const kvx_run *__restrict__ run
     }
 }
 
+// ---------------------------------------------------------------------------
+// xpose: pages that are not [token][head][dim] inside
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t unit_offset(const XposeSide &g, uint32_t u) {
+    // u < 65536 and units_per_granule < 65536 make the multiply-high division exact
+    const uint32_t q = g.units_per_granule == 1u ? u : __umulhi(u, g.granule_magic);
+    return (uint64_t)q * g.granule_step + (uint64_t)(u - q * g.units_per_granule) * 16u;
+}
+
+// Cell c of a tile -> (token, unit) inside the tile.  On a token-fast side consecutive lanes walk the
+// tokens of one unit column, otherwise the units of one token.
+template <bool TOKEN_FAST>
+__device__ __forceinline__ void cell_to_tu(uint32_t c, uint32_t log2_tt, uint32_t log2_uu, uint32_t &t, uint32_t &u) {
+    if (TOKEN_FAST) {
+        t = c & ((1u << log2_tt) - 1u);
+        u = c >> log2_tt;
+    } else {
+        u = c & ((1u << log2_uu) - 1u);
+        t = c >> log2_uu;
+    }
+}
+
+template <bool SRC_TF, bool DST_TF, bool NT>
+__global__ __launch_bounds__(kXposeThreads) void xpose_kernel(const kvx_run *__restrict__ runs,
+                                                              const char *__restrict__ src,
+                                                              char *__restrict__ dst, XposeParams p) {
+    constexpr int kPerLane = kXposeCells / kXposeThreads;
+    // [token][unit] with one unit of padding per token row, so that a column walk spreads over the banks
+    __shared__ u32x4 stage[(SRC_TF != DST_TF) ? kXposeCells + 64 : 1];
+    const uint32_t pitch = (1u << p.log2_uu) + 1u;
+    const uint32_t tiles_per_run = p.tiles_t * p.tiles_u;
+
+    uint32_t first = blockIdx.x;
+    if (p.swizzle_chunk) first = (blockIdx.x & 7u) * p.swizzle_chunk + (blockIdx.x >> 3);
+
+    for (uint64_t v64 = first; v64 < p.total_tiles; v64 += gridDim.x) {
+        const uint32_t v = (uint32_t)v64;
+        const uint32_t sidx = v % tiles_per_run;
+        const uint32_t q = v / tiles_per_run;
+        uint32_t lc, e;
+        if (p.order == 2) {
+            const uint32_t i = q % p.group;
+            const uint32_t q2 = q / p.group;
+            lc = q2 % p.num_lc;
+            e = (q2 / p.num_lc) * p.group + i;
+        } else {
+            e = q % p.num_runs;
+            lc = q / p.num_runs;
+        }
+        lc += p.lc_first;
+        const kvx_run run = runs[e];
+        const uint32_t tokens = run.bytes / p.row;
+        const uint32_t t0 = (sidx / p.tiles_u) << p.log2_tt;
+        const uint32_t u0 = (sidx % p.tiles_u) << p.log2_uu;
+        if (t0 >= tokens) continue; // uniform over the workgroup: no barrier is skipped by part of it
+
+        const uint32_t layer = p.layer_begin + (lc >> 1);
+        const uint32_t kv = lc & 1u;
+        const uint64_t seg = (uint64_t)lc * run.seq_len * p.row;
+        const char *sp = src + run.src_off + (p.s.is_buf ? seg : layer * p.s.stride_layer + kv * p.s.stride_kv);
+        char *dp = dst + run.dst_off + (p.d.is_buf ? seg : layer * p.d.stride_layer + kv * p.d.stride_kv);
+
+        u32x4 r[kPerLane];
+        bool ok[kPerLane];
+#pragma unroll
+        for (int k = 0; k < kPerLane; ++k) {
+            uint32_t t, u;
+            cell_to_tu<SRC_TF>(k * kXposeThreads + threadIdx.x, p.log2_tt, p.log2_uu, t, u);
+            ok[k] = (t0 + t < tokens) && (u0 + u < p.units_per_row);
+            if (ok[k]) r[k] = ld16<NT>(sp + (uint64_t)(t0 + t) * p.s.token_step + unit_offset(p.s, u0 + u));
+        }
+        if (SRC_TF == DST_TF) {
+#pragma unroll
+            for (int k = 0; k < kPerLane; ++k) {
+                uint32_t t, u;
+                cell_to_tu<DST_TF>(k * kXposeThreads + threadIdx.x, p.log2_tt, p.log2_uu, t, u);
+                if (ok[k]) st16<NT>(dp + (uint64_t)(t0 + t) * p.d.token_step + unit_offset(p.d, u0 + u), r[k]);
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < kPerLane; ++k) {
+                uint32_t t, u;
+                cell_to_tu<SRC_TF>(k * kXposeThreads + threadIdx.x, p.log2_tt, p.log2_uu, t, u);
+                if (ok[k]) stage[t * pitch + u] = r[k];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < kPerLane; ++k) {
+                uint32_t t, u;
+                cell_to_tu<DST_TF>(k * kXposeThreads + threadIdx.x, p.log2_tt, p.log2_uu, t, u);
+                if ((t0 + t < tokens) && (u0 + u < p.units_per_row))
+                    st16<NT>(dp + (uint64_t)(t0 + t) * p.d.token_step + unit_offset(p.d, u0 + u),
+                             stage[t * pitch + u]);
+            }
+            __syncthreads(); // the next tile of this workgroup reuses the stage
+        }
+    }
+}
+
 // Plain contiguous copy with the data mover's access shape: the yardstick.
 template <int T, int U, bool NT>
 __global__ __launch_bounds__(T) void plain_copy_kernel(const char *__restrict__ src, char *__restrict__ dst,
@@ -355,6 +458,29 @@ hipError_t launch_copy(const CopyParams &p, uint32_t threads, uint32_t unroll, b
     case 1024: return copy_t<1024>(p, unroll, nontemporal, grid, lds_bytes, stream);
     default: return hipErrorInvalidValue;
     }
+}
+
+namespace {
+template <bool S, bool D>
+hipError_t xpose_sd(const XposeParams &p, bool nt, uint32_t grid, hipStream_t stream) {
+    if (nt)
+        hipLaunchKernelGGL((xpose_kernel<S, D, true>), dim3(grid), dim3(kXposeThreads), 0, stream, p.runs, p.src,
+                           p.dst, p);
+    else
+        hipLaunchKernelGGL((xpose_kernel<S, D, false>), dim3(grid), dim3(kXposeThreads), 0, stream, p.runs, p.src,
+                           p.dst, p);
+    return hipGetLastError();
+}
+} // namespace
+
+hipError_t launch_xpose(const XposeParams &p, bool src_token_fast, bool dst_token_fast, bool nontemporal,
+                        uint32_t grid, hipStream_t stream) {
+    if (p.total_tiles == 0 || grid == 0) return hipSuccess;
+    if (src_token_fast)
+        return dst_token_fast ? xpose_sd<true, true>(p, nontemporal, grid, stream)
+                              : xpose_sd<true, false>(p, nontemporal, grid, stream);
+    return dst_token_fast ? xpose_sd<false, true>(p, nontemporal, grid, stream)
+                          : xpose_sd<false, false>(p, nontemporal, grid, stream);
 }
 
 hipError_t launch_plain_copy(char *dst, const char *src, uint64_t bytes, uint32_t threads, uint32_t unroll,

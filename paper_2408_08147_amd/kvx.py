@@ -17,6 +17,7 @@ from . import build as _build
 
 OK, ERR_INVALID_ARG, ERR_ALIGNMENT, ERR_BLOCK_TABLE, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_DEVICE = range(7)
 LAYOUT_LAYER_MAJOR, LAYOUT_PAGE_MAJOR = 0, 1
+INNER_TOKEN_ROWS, INNER_HEAD_MAJOR, INNER_DIM_SPLIT_TOKEN = 0, 1, 2
 OP_PACK, OP_UNPACK, OP_CONVERT = 0, 1, 2
 
 EXPORTS = (
@@ -37,7 +38,7 @@ class KvxError(RuntimeError):
 class PoolDesc(C.Structure):
     _fields_ = [("num_layers", C.c_uint32), ("num_kv_heads", C.c_uint32), ("head_dim", C.c_uint32),
                 ("elem_bytes", C.c_uint32), ("page_tokens", C.c_uint32), ("num_pages", C.c_uint32),
-                ("layout", C.c_uint32), ("reserved", C.c_uint32),
+                ("layout", C.c_uint32), ("inner", C.c_uint32),
                 ("stride_layer", C.c_uint64), ("stride_kv", C.c_uint64),
                 ("stride_page", C.c_uint64), ("stride_token", C.c_uint64)]
 
@@ -283,6 +284,6 @@ def kvx_copy_yardstick(dst: int, src: int, nbytes: int, stream: int = 0, unroll:
 
 def pool_desc(num_layers: int, num_kv_heads: int, head_dim: int, elem_bytes: int, page_tokens: int,
               num_pages: int, layout: int = LAYOUT_LAYER_MAJOR,
-              strides: Sequence[int] = (0, 0, 0, 0)) -> PoolDesc:
-    return PoolDesc(num_layers, num_kv_heads, head_dim, elem_bytes, page_tokens, num_pages, layout, 0,
+              strides: Sequence[int] = (0, 0, 0, 0), inner: int = INNER_TOKEN_ROWS) -> PoolDesc:
+    return PoolDesc(num_layers, num_kv_heads, head_dim, elem_bytes, page_tokens, num_pages, layout, inner,
                     *strides)

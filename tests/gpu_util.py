@@ -24,6 +24,7 @@ class Side:
     layout: int = 0
     strides: Tuple[int, int, int, int] = (0, 0, 0, 0)
     span_bytes: int = 0          # allocation size when strides are explicit
+    inner: int = 0               # arrangement inside a page (0 rows, 1 head-major, 2 token axis in 16-byte groups)
 
 
 @dataclass
@@ -51,11 +52,11 @@ class Case:
 
     def kvx_pool(self, side: Side):
         return kvx.pool_desc(self.num_layers, self.num_kv_heads, self.head_dim, self.elem_bytes,
-                             side.page_tokens, side.num_pages, side.layout, side.strides)
+                             side.page_tokens, side.num_pages, side.layout, side.strides, side.inner)
 
     def oracle_pool(self, side: Side):
         return kvxo.Pool(self.num_layers, self.num_kv_heads, self.head_dim, self.elem_bytes,
-                         side.page_tokens, side.num_pages, side.layout, *side.strides)
+                         side.page_tokens, side.num_pages, side.layout, *side.strides, inner=side.inner)
 
 
 def tables(rng, seq_lens, P, num_pages, unique=True, extra=0):
@@ -70,14 +71,16 @@ def tables(rng, seq_lens, P, num_pages, unique=True, extra=0):
     return np.array([x for r in rows for x in r], dtype=np.uint32), offs
 
 
-def make_case(rng, L, H, D, e, lens, Ps, Pd, ls=0, ld=0, shared_src=False, extra=0, slack_pages=3):
+def make_case(rng, L, H, D, e, lens, Ps, Pd, ls=0, ld=0, shared_src=False, extra=0, slack_pages=3,
+              inner_s=0, inner_d=0):
     lens = np.asarray(lens, dtype=np.uint32)
     used_s = int(sum((int(n) + Ps - 1) // Ps + extra for n in lens))
     used_d = int(sum((int(n) + Pd - 1) // Pd + extra for n in lens))
     nps, npd = 2 * used_s + slack_pages, 2 * used_d + slack_pages
     ids_s, offs_s = tables(rng, lens, Ps, nps, unique=not shared_src, extra=extra)
     ids_d, offs_d = tables(rng, lens, Pd, npd, unique=True, extra=extra)
-    return Case(L, H, D, e, lens, Side(Ps, nps, ls), Side(Pd, npd, ld), ids_s, offs_s, ids_d, offs_d)
+    return Case(L, H, D, e, lens, Side(Ps, nps, ls, inner=inner_s), Side(Pd, npd, ld, inner=inner_d),
+                ids_s, offs_s, ids_d, offs_d)
 
 
 @dataclass

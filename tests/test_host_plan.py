@@ -67,6 +67,24 @@ def test_argument_errors():
     expect(kvx.ERR_UNSUPPORTED, kvx.kvx_plan, huge, kvx.BatchDesc([1], [0], [0, 1]), None, None, 0, 1)
 
 
+def test_inner_arrangement_errors():
+    _, b = _simple()
+    ok = kvx.pool_desc(2, 8, 128, 2, 16, 64, inner=kvx.INNER_DIM_SPLIT_TOKEN)
+    kvx.kvx_plan(ok, b, ok, b, 0, 2).destroy()
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, kvx.pool_desc(2, 8, 128, 2, 16, 64, inner=3), b, None, None, 0, 2)
+    strided = kvx.pool_desc(2, 8, 128, 2, 16, 64, strides=(1 << 22, 1 << 21, 1 << 15, 2048), inner=1)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, strided, b, None, None, 0, 2)
+    # head_dim*elem_bytes must be a multiple of 16 even when the whole row is
+    expect(kvx.ERR_ALIGNMENT, kvx.kvx_plan, kvx.pool_desc(2, 4, 4, 2, 16, 64, inner=1), b, None, None, 0, 2)
+    # 16-byte groups need an element size that divides 16
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, kvx.pool_desc(2, 1, 16, 3, 16, 64, inner=2), b, None, None, 0, 2)
+    # the two sides may differ in arrangement, not in shape
+    other = kvx.pool_desc(2, 8, 128, 2, 8, 128, layout=1, inner=kvx.INNER_HEAD_MAJOR)
+    b8 = kvx.BatchDesc([100, 33], np.arange(18), [0, 13, 18])
+    p = kvx.kvx_plan(ok, b, other, b8, 0, 2)
+    assert kvx.kvx_plan_total_bytes(p) == 133 * 2 * 2 * 2048
+
+
 def test_sides_must_agree():
     s, b = _simple()
     d_heads = kvx.pool_desc(2, 4, 128, 2, 16, 64)
