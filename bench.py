@@ -54,9 +54,9 @@ class Setup:
         self.dev = torch.device("cuda:0")
         self.stream = torch.cuda.Stream(device=self.dev)
         self.sp = kvx.pool_desc(w.num_layers, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_s,
-                                b.num_pages_s, w.layout_s)
+                                b.num_pages_s, w.layout_s, inner=w.inner_s)
         self.dp = kvx.pool_desc(w.num_layers, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_d,
-                                b.num_pages_d, w.layout_d)
+                                b.num_pages_d, w.layout_d, inner=w.inner_d)
         self.sb = kvx.BatchDesc(b.seq_lens, b.ids_s, b.offs_s)
         self.db = kvx.BatchDesc(b.seq_lens, b.ids_d, b.offs_d)
         self.ws_bytes = kvx.kvx_plan_workspace_bytes(self.sp, self.sb, self.dp, self.db)

@@ -6,6 +6,8 @@
            against ONE planned kernel launch, over a sweep of page sizes at fixed tokens
   layers   per-layer triggers (section 3.6): the whole model in one launch, one launch per layer on the
            same plan and buffer, and the same with the grid capped to a share of the compute units
+  layouts  pools whose pages are head-major or keep the token axis inside 16-byte groups of the head
+           dimension, against plain [token][head][dim] pages of the same shape
 """
 import argparse
 import json
@@ -83,16 +85,43 @@ def study_layers(args):
     p.destroy()
 
 
+def study_layouts(args):
+    from paper_2408_08147_amd import workloads as W
+    names = {0: "rows", 1: "head_major", 2: "dim_split_token"}
+    shapes = [("workload2 shape, 128-token pages", W.CONFIGS[2], {}),
+              ("workload2 shape, 16-token pages", W.CONFIGS[2], dict(page_s=16, page_d=16)),
+              ("workload2 shape, 128 -> 16 tokens, page-major receiver", W.CONFIGS[2],
+               dict(page_d=16, layout_d=W.PAGE_MAJOR)),
+              ("workload3 shape (one head, 256-byte rows)", W.CONFIGS[3], {})]
+    for label, base, kw in shapes:
+        for ins, ind in [(0, 0), (0, 1), (1, 0), (0, 2), (2, 0), (2, 2), (1, 2)]:
+            w = base.scaled(inner_s=ins, inner_d=ind, **kw)
+            s = bench.Setup(w, fill=False)
+            p = s.plan()
+            tp = s.time_op(lambda: s.pack(p), iters=8, warmup=2)
+            tu = s.time_op(lambda: s.unpack(p), iters=8, warmup=2)
+            tc = s.time_op(lambda: s.convert(p), iters=8, warmup=2)
+            p.destroy()
+            g = lambda ms: round(2 * s.payload / ms / 1e6, 1)
+            print(json.dumps({"study": "layouts", "shape": label, "sender_pages": names[ins],
+                              "receiver_pages": names[ind], "payload_bytes": s.payload,
+                              "pack_hbm_GBps": g(tp), "unpack_hbm_GBps": g(tu), "convert_hbm_GBps": g(tc)}),
+                  flush=True)
+            del s
+            import torch
+            torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["blocks", "layers"])
+    ap.add_argument("study", choices=["blocks", "layers", "layouts"])
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 5])
     ap.add_argument("--layers", type=int, default=8, help="blocks: layers of the workload-2 shape to move")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench_studies.py: no GPU visible")
-    {"blocks": study_blocks, "layers": study_layers}[args.study](args)
+    {"blocks": study_blocks, "layers": study_layers, "layouts": study_layouts}[args.study](args)
 
 
 if __name__ == "__main__":

@@ -111,7 +111,9 @@ typedef struct {
 } kvx_batch_desc;
 
 /* Launch configuration of the copy kernels.  Zero in a field = library default.
- * It changes speed only, never results. */
+ * It changes speed only, never results.  `unroll`, `threads`, `workgroups_per_cu`
+ * and `xcd_block_tiles` shape the kernel for [token][head][dim] pages only; the
+ * kernel for other page arrangements has a fixed tile of 1024 16-byte units. */
 typedef struct {
     uint32_t unroll;        /* 16-byte loads in flight per lane before the first store: 1,2,4,8; 0 = chosen
                                per operation together with `threads` */

@@ -22,7 +22,7 @@
  *   total    the KV size formula of section 2.1: bytes per layer =
  *            elem_bytes * hidden * 2 (K and V) * tokens.
  *
- * Readings where the paper is silent (also listed in the design notes):
+ * Readings where the paper is silent:
  *   - a token row [head][dim] is contiguous, row = heads*dim*elem_bytes;
  *   - inside a request's buffer: layers ascending, per layer all K rows then
  *     all V rows, tokens ascending;

@@ -48,6 +48,8 @@ class Workload:
     ln_sigma: float = 0.0
     pool_pages_fixed: int = 0  # >0: fixed pool size in pages (both sides)
     pool_factor: float = 2.0   # else pages = ceil(factor * used pages)
+    inner_s: int = 0           # arrangement inside a page, per side: 0 [token][head][dim],
+    inner_d: int = 0           # 1 [head][token][dim], 2 [head][dim/x][token][x] (x elements = 16 bytes)
 
     @property
     def row_bytes(self) -> int:
