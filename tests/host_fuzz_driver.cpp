@@ -1,0 +1,108 @@
+// Host-only fuzz driver for the validation and plan arithmetic of libkvx, built with
+// AddressSanitizer and UndefinedBehaviorSanitizer on the host side (tests/test_host_sanitizers.py).
+// It never launches a kernel: every plan is host-only (no device workspace).
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+#include "kvx.h"
+
+static uint64_t state = 0x9E3779B97F4A7C15ull;
+static uint64_t rnd() {
+    state ^= state << 13;
+    state ^= state >> 7;
+    state ^= state << 17;
+    return state;
+}
+static uint32_t below(uint32_t n) { return n ? (uint32_t)(rnd() % n) : 0; }
+
+int main(int argc, char **argv) {
+    const int iters = argc > 1 ? atoi(argv[1]) : 20000;
+    long ok = 0, rejected = 0;
+    for (int it = 0; it < iters; ++it) {
+        kvx_pool_desc s{}, d{};
+        const uint32_t elems[] = {1, 2, 4, 3, 8};
+        s.num_layers = 1 + below(8);
+        s.num_kv_heads = below(20) == 0 ? 0 : 1 + below(8);
+        s.head_dim = 8u << below(5);
+        s.elem_bytes = elems[below(5)];
+        s.page_tokens = below(30) == 0 ? 0 : 1 + below(40);
+        s.num_pages = 1 + below(300);
+        s.layout = below(12) == 0 ? 5 : below(2);
+        s.inner = below(15) == 0 ? 3 : below(3);
+        d = s;
+        d.page_tokens = 1 + below(40);
+        d.num_pages = 1 + below(300);
+        d.layout = below(2);
+        d.inner = below(3);
+        if (below(10) == 0) d.head_dim *= 2;
+        if (below(10) == 0) { // explicit strides, sometimes inconsistent
+            const uint64_t row = (uint64_t)s.num_kv_heads * s.head_dim * s.elem_bytes;
+            s.stride_token = row + 16 * below(3) - (below(8) == 0 ? 8 : 0);
+            s.stride_page = s.stride_token * s.page_tokens + 32 * below(2);
+            s.stride_kv = s.stride_page * s.num_pages;
+            s.stride_layer = below(9) == 0 ? 0 : 2 * s.stride_kv;
+        }
+        const uint32_t R = below(7);
+        std::vector<uint32_t> lens(R), ids_s, ids_d;
+        std::vector<uint64_t> offs_s(R + 1, 0), offs_d(R + 1, 0);
+        for (uint32_t r = 0; r < R; ++r) {
+            lens[r] = below(5) == 0 ? 0 : below(400);
+            const uint32_t ps = s.page_tokens ? s.page_tokens : 1, pd = d.page_tokens;
+            uint32_t ns = (lens[r] + ps - 1) / ps + below(3), nd = (lens[r] + pd - 1) / pd + below(3);
+            if (below(25) == 0 && ns) --ns; // too short now and then
+            if (below(25) == 0 && nd) --nd;
+            for (uint32_t j = 0; j < ns; ++j) ids_s.push_back(below(s.num_pages + (below(40) == 0 ? 3 : 0)));
+            for (uint32_t j = 0; j < nd; ++j) ids_d.push_back(below(d.num_pages + (below(40) == 0 ? 3 : 0)));
+            offs_s[r + 1] = ids_s.size();
+            offs_d[r + 1] = ids_d.size();
+        }
+        kvx_batch_desc sb{R, 0, lens.data(), ids_s.data(), offs_s.data()};
+        kvx_batch_desc db{R, 0, lens.data(), ids_d.data(), offs_d.data()};
+        const uint32_t l0 = below(s.num_layers + 1), l1 = below(s.num_layers + 2);
+        const int mode = below(3);
+        size_t ws = 0;
+        (void)kvx_plan_workspace_bytes(mode != 1 ? &s : nullptr, mode != 1 ? &sb : nullptr,
+                                       mode != 0 ? &d : nullptr, mode != 0 ? &db : nullptr, &ws);
+        kvx_plan_t *plan = nullptr;
+        kvx_status st = kvx_plan(mode != 1 ? &s : nullptr, mode != 1 ? &sb : nullptr, mode != 0 ? &d : nullptr,
+                                 mode != 0 ? &db : nullptr, l0, l1, nullptr, 0, nullptr, &plan);
+        if (st != KVX_OK) {
+            if (plan) { printf("plan returned on failure\n"); return 1; }
+            (void)kvx_status_string(st);
+            ++rejected;
+            continue;
+        }
+        ++ok;
+        uint64_t total = 0, off = 0, len = 0, sum = 0;
+        if (kvx_plan_total_bytes(plan, &total) != KVX_OK) return 1;
+        for (uint32_t r = 0; r < R; ++r) {
+            if (kvx_plan_request_segment(plan, r, &off, &len) != KVX_OK || off != sum) {
+                printf("request segments do not tile the buffer\n");
+                return 1;
+            }
+            uint64_t inner = off;
+            for (uint32_t l = l0; l < l1; ++l) {
+                uint64_t o2, n2;
+                if (kvx_plan_segment(plan, r, l, &o2, &n2) != KVX_OK || o2 != inner) {
+                    printf("layer segments do not tile the request\n");
+                    return 1;
+                }
+                inner += n2;
+            }
+            if (inner != off + len) { printf("layer segments do not fill the request\n"); return 1; }
+            sum += len;
+        }
+        if (sum != total) { printf("segments do not add up to the total\n"); return 1; }
+        (void)kvx_plan_segment(plan, R, l0, &off, &len);
+        kvx_launch_cfg cfg{};
+        cfg.unroll = below(10);
+        cfg.threads = 64u << below(6);
+        (void)kvx_plan_set_launch(plan, &cfg);
+        if (kvx_pack(plan, &s, &d, total, nullptr) == KVX_OK && total) { printf("host-only plan launched\n"); return 1; }
+        kvx_plan_destroy(plan);
+    }
+    printf("fuzz done: %ld plans accepted, %ld rejected\n", ok, rejected);
+    return ok > 100 && rejected > 100 ? 0 : 2;
+}

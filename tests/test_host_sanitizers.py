@@ -1,0 +1,26 @@
+"""Builds the library's host side together with a fuzz driver under
+AddressSanitizer and UndefinedBehaviorSanitizer (host code only; device code is
+compiled as usual and never runs) and lets it hammer kvx_plan's validation with
+random, partly malformed descriptors and block tables."""
+import os
+import subprocess
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_host_validation_under_asan_ubsan(tmp_path):
+    exe = tmp_path / "kvx_host_fuzz"
+    csrc = os.path.join(ROOT, "paper_2408_08147_amd", "csrc")
+    cmd = ["/opt/rocm/bin/hipcc", "--offload-arch=gfx950", "-O1", "-g", "-std=c++17",
+           "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+           "-I", os.path.join(ROOT, "include"), "-I", csrc,
+           "-x", "hip", os.path.join(csrc, "kvx_api.cpp"), os.path.join(csrc, "kvx_kernels.hip"),
+           os.path.join(ROOT, "tests", "host_fuzz_driver.cpp"), "-o", str(exe)]
+    build = subprocess.run(cmd, capture_output=True, text=True)
+    assert build.returncode == 0, build.stderr[-3000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    run = subprocess.run([str(exe), "20000"], capture_output=True, text=True, env=env, timeout=300)
+    assert run.returncode == 0, (run.stdout[-2000:], run.stderr[-4000:])
+    assert "fuzz done" in run.stdout
