@@ -61,7 +61,8 @@ typedef enum {
                                 listed twice, CSR offsets not ascending */
     KVX_ERR_CAPACITY = 4,    /* buffer or workspace too small */
     KVX_ERR_UNSUPPORTED = 5, /* a size beyond what the kernels index (see kvx_plan) */
-    KVX_ERR_DEVICE = 6       /* a HIP call failed; hipGetLastError has the detail */
+    KVX_ERR_DEVICE = 6,      /* a HIP call failed; hipGetLastError has the detail */
+    KVX_ERR_BUSY = 7         /* kvx_retriever_acquire: every receive slot is in flight */
 } kvx_status;
 
 typedef enum {
@@ -253,6 +254,59 @@ kvx_status kvx_convert_layers(const kvx_plan_t *plan, uint32_t layer_begin, uint
  * sender pools with [token][head][dim] pages (else KVX_ERR_UNSUPPORTED). */
 kvx_status kvx_pack_blockwise(const kvx_plan_t *plan, const void *src_pool, void *buf, uint64_t buf_bytes,
                               uint32_t confirm_every, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * Asynchronous retrieval (section 3.6, "Asynchronous Retrieval"): the decoding
+ * side has little memory to spare for transfers in flight, so incoming KV waits
+ * in a small number of receive slots; a retrieval runs beside the running
+ * batch on a stream of its own, and when it completes the slot is free for the
+ * next one while the request becomes valid in the next decoding iteration.
+ *
+ * A retriever owns num_slots streams (default priority, non-blocking) and
+ * events; the caller owns the arena [device], which is cut into num_slots
+ * equal parts, each a receive buffer of slot_buf_bytes followed by a plan
+ * workspace of slot_ws_bytes (both rounded up to 256 bytes; kvx_retriever_arena_bytes
+ * gives the total).  One retrieval is
+ *     acquire  -> the caller lets the bytes arrive in the slot's buffer, on the
+ *                 slot's stream (an RDMA write in the paper; here any copy or
+ *                 kvx_pack) -> scatter (plan + kvx_unpack on the slot's stream)
+ *     poll     -> tickets whose scatter has completed; their slots are free again
+ * Calls on one retriever must come from one thread at a time. */
+typedef struct kvx_retriever_s kvx_retriever_t;
+
+kvx_status kvx_retriever_arena_bytes(uint32_t num_slots, uint64_t slot_buf_bytes, uint64_t slot_ws_bytes,
+                                     uint64_t *out_bytes);
+kvx_status kvx_retriever_create(uint32_t num_slots, uint64_t slot_buf_bytes, uint64_t slot_ws_bytes,
+                                void *dev_arena, uint64_t arena_bytes, kvx_retriever_t **out);
+/* Waits for everything in flight, then releases streams and events. */
+void kvx_retriever_destroy(kvx_retriever_t *ret);
+
+/* Takes a free slot for a transfer of need_bytes, tagged with the caller's
+ * ticket.  KVX_ERR_BUSY if none is free (poll first), KVX_ERR_CAPACITY if
+ * need_bytes exceeds a slot's buffer.  Returns the slot's buffer [device] and
+ * stream, on which the caller enqueues whatever makes the bytes arrive. */
+kvx_status kvx_retriever_acquire(kvx_retriever_t *ret, uint64_t ticket, uint64_t need_bytes, uint32_t *slot,
+                                 void **slot_buf, void **slot_stream);
+
+/* RecvScatter of the slot's buffer into dst_pool [device] for the receiver's
+ * geometry `d`, batch `db` and layers [layer_begin, layer_end): builds the plan
+ * in the slot's workspace and enqueues kvx_unpack, both on the slot's stream,
+ * behind whatever the caller enqueued there.  `launch` may be NULL; a capped
+ * grid (max_workgroups) keeps most of the device for the running batch.  On an
+ * error the slot stays acquired; release it with kvx_retriever_abandon. */
+kvx_status kvx_retriever_scatter(kvx_retriever_t *ret, uint32_t slot, const kvx_pool_desc *d,
+                                 const kvx_batch_desc *db, uint32_t layer_begin, uint32_t layer_end,
+                                 void *dst_pool, const kvx_launch_cfg *launch);
+
+/* Gives an acquired slot back without scattering (waits for its stream). */
+kvx_status kvx_retriever_abandon(kvx_retriever_t *ret, uint32_t slot);
+
+/* Non-blocking.  Writes up to `capacity` tickets whose scatter has completed
+ * since they were last reported and frees their slots. */
+kvx_status kvx_retriever_poll(kvx_retriever_t *ret, uint64_t *tickets, uint32_t capacity, uint32_t *count);
+
+/* Blocks until nothing is in flight; completed tickets stay to be polled. */
+kvx_status kvx_retriever_drain(kvx_retriever_t *ret);
 
 /* Yardstick, not part of the transfer: a plain contiguous device-to-device copy
  * of `bytes` bytes (a multiple of 16; both pointers [device], 16-byte aligned,

@@ -6,7 +6,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvx.so")
-SOURCES = [os.path.join(CSRC, "kvx_api.cpp"), os.path.join(CSRC, "kvx_kernels.hip")]
+SOURCES = [os.path.join(CSRC, "kvx_api.cpp"), os.path.join(CSRC, "kvx_retriever.cpp"),
+           os.path.join(CSRC, "kvx_kernels.hip")]
 HEADERS = [os.path.join(CSRC, "kvx_internal.h"), os.path.join(ROOT, "include", "kvx.h")]
 
 

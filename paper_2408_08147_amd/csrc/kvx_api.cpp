@@ -349,6 +349,7 @@ const char *kvx_status_string(kvx_status st) {
     case KVX_ERR_CAPACITY: return "buffer or workspace too small";
     case KVX_ERR_UNSUPPORTED: return "size not supported";
     case KVX_ERR_DEVICE: return "HIP error";
+    case KVX_ERR_BUSY: return "every receive slot is in flight";
     }
     return "unknown status";
 }

@@ -1,0 +1,161 @@
+// Receive slots for asynchronous retrieval (paper section 3.6, "Asynchronous Retrieval"): a small,
+// fixed number of in-flight transfers on the decoding side, each on a stream of its own, completion found
+// by polling events.  Host code only; the data moves through kvx_plan + kvx_unpack.
+#include <hip/hip_runtime.h>
+
+#include <new>
+#include <vector>
+
+#include "kvx.h"
+
+namespace {
+constexpr uint64_t kAlign = 256;
+inline uint64_t align_up(uint64_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+enum SlotState : uint32_t { SLOT_FREE = 0, SLOT_ACQUIRED = 1, SLOT_SCATTERING = 2 };
+
+struct Slot {
+    SlotState state = SLOT_FREE;
+    uint64_t ticket = 0;
+    char *buf = nullptr;
+    char *ws = nullptr;
+    hipStream_t stream = nullptr;
+    hipEvent_t done = nullptr;
+};
+} // namespace
+
+struct kvx_retriever_s {
+    std::vector<Slot> slots;
+    uint64_t buf_bytes = 0, ws_bytes = 0;
+};
+
+extern "C" {
+
+kvx_status kvx_retriever_arena_bytes(uint32_t num_slots, uint64_t slot_buf_bytes, uint64_t slot_ws_bytes,
+                                     uint64_t *out_bytes) {
+    if (!num_slots || !slot_buf_bytes || !slot_ws_bytes || !out_bytes) return KVX_ERR_INVALID_ARG;
+    *out_bytes = num_slots * (align_up(slot_buf_bytes) + align_up(slot_ws_bytes));
+    return KVX_OK;
+}
+
+kvx_status kvx_retriever_create(uint32_t num_slots, uint64_t slot_buf_bytes, uint64_t slot_ws_bytes,
+                                void *dev_arena, uint64_t arena_bytes, kvx_retriever_t **out) {
+    if (!out) return KVX_ERR_INVALID_ARG;
+    *out = nullptr;
+    uint64_t need = 0;
+    kvx_status st = kvx_retriever_arena_bytes(num_slots, slot_buf_bytes, slot_ws_bytes, &need);
+    if (st != KVX_OK) return st;
+    if (!dev_arena || num_slots > 1024) return KVX_ERR_INVALID_ARG;
+    if ((uintptr_t)dev_arena % kAlign) return KVX_ERR_ALIGNMENT;
+    if (arena_bytes < need) return KVX_ERR_CAPACITY;
+    kvx_retriever_s *r = new (std::nothrow) kvx_retriever_s;
+    if (!r) return KVX_ERR_INVALID_ARG;
+    r->buf_bytes = align_up(slot_buf_bytes);
+    r->ws_bytes = align_up(slot_ws_bytes);
+    r->slots.resize(num_slots);
+    char *base = static_cast<char *>(dev_arena);
+    for (uint32_t i = 0; i < num_slots; ++i) {
+        Slot &s = r->slots[i];
+        s.buf = base + i * (r->buf_bytes + r->ws_bytes);
+        s.ws = s.buf + r->buf_bytes;
+        // default priority on purpose: streams of mixed priorities are not used anywhere in this library
+        if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&s.done, hipEventDisableTiming) != hipSuccess) {
+            kvx_retriever_destroy(r);
+            return KVX_ERR_DEVICE;
+        }
+    }
+    *out = r;
+    return KVX_OK;
+}
+
+void kvx_retriever_destroy(kvx_retriever_t *ret) {
+    if (!ret) return;
+    for (Slot &s : ret->slots) {
+        if (s.stream) {
+            (void)hipStreamSynchronize(s.stream);
+            (void)hipStreamDestroy(s.stream);
+        }
+        if (s.done) (void)hipEventDestroy(s.done);
+    }
+    delete ret;
+}
+
+kvx_status kvx_retriever_acquire(kvx_retriever_t *ret, uint64_t ticket, uint64_t need_bytes, uint32_t *slot,
+                                 void **slot_buf, void **slot_stream) {
+    if (!ret || !slot || !slot_buf || !slot_stream) return KVX_ERR_INVALID_ARG;
+    if (need_bytes > ret->buf_bytes) return KVX_ERR_CAPACITY;
+    for (uint32_t i = 0; i < ret->slots.size(); ++i) {
+        Slot &s = ret->slots[i];
+        if (s.state != SLOT_FREE) continue;
+        s.state = SLOT_ACQUIRED;
+        s.ticket = ticket;
+        *slot = i;
+        *slot_buf = s.buf;
+        *slot_stream = s.stream;
+        return KVX_OK;
+    }
+    return KVX_ERR_BUSY;
+}
+
+kvx_status kvx_retriever_scatter(kvx_retriever_t *ret, uint32_t slot, const kvx_pool_desc *d,
+                                 const kvx_batch_desc *db, uint32_t layer_begin, uint32_t layer_end,
+                                 void *dst_pool, const kvx_launch_cfg *launch) {
+    if (!ret || slot >= ret->slots.size() || !d || !db || !dst_pool) return KVX_ERR_INVALID_ARG;
+    Slot &s = ret->slots[slot];
+    if (s.state != SLOT_ACQUIRED) return KVX_ERR_INVALID_ARG;
+    size_t ws_need = 0;
+    kvx_status st = kvx_plan_workspace_bytes(nullptr, nullptr, d, db, &ws_need);
+    if (st != KVX_OK) return st;
+    if (ws_need > ret->ws_bytes) return KVX_ERR_CAPACITY;
+    kvx_plan_t *plan = nullptr;
+    st = kvx_plan(nullptr, nullptr, d, db, layer_begin, layer_end, s.ws, ret->ws_bytes, s.stream, &plan);
+    if (st != KVX_OK) return st;
+    uint64_t total = 0;
+    (void)kvx_plan_total_bytes(plan, &total);
+    if (total > ret->buf_bytes) {
+        kvx_plan_destroy(plan);
+        return KVX_ERR_CAPACITY;
+    }
+    if (launch) st = kvx_plan_set_launch(plan, launch);
+    if (st == KVX_OK) st = kvx_unpack(plan, s.buf, ret->buf_bytes, dst_pool, s.stream);
+    kvx_plan_destroy(plan); // the launch carries its arguments; the workspace stays with the slot
+    if (st != KVX_OK) return st;
+    if (hipEventRecord(s.done, s.stream) != hipSuccess) return KVX_ERR_DEVICE;
+    s.state = SLOT_SCATTERING;
+    return KVX_OK;
+}
+
+kvx_status kvx_retriever_abandon(kvx_retriever_t *ret, uint32_t slot) {
+    if (!ret || slot >= ret->slots.size()) return KVX_ERR_INVALID_ARG;
+    Slot &s = ret->slots[slot];
+    if (s.state != SLOT_ACQUIRED) return KVX_ERR_INVALID_ARG;
+    if (hipStreamSynchronize(s.stream) != hipSuccess) return KVX_ERR_DEVICE;
+    s.state = SLOT_FREE;
+    return KVX_OK;
+}
+
+kvx_status kvx_retriever_poll(kvx_retriever_t *ret, uint64_t *tickets, uint32_t capacity, uint32_t *count) {
+    if (!ret || !count || (capacity && !tickets)) return KVX_ERR_INVALID_ARG;
+    uint32_t n = 0;
+    for (Slot &s : ret->slots) {
+        if (n >= capacity) break;
+        if (s.state != SLOT_SCATTERING) continue;
+        const hipError_t e = hipEventQuery(s.done);
+        if (e == hipErrorNotReady) continue;
+        if (e != hipSuccess) return KVX_ERR_DEVICE;
+        tickets[n++] = s.ticket;
+        s.state = SLOT_FREE;
+    }
+    *count = n;
+    return KVX_OK;
+}
+
+kvx_status kvx_retriever_drain(kvx_retriever_t *ret) {
+    if (!ret) return KVX_ERR_INVALID_ARG;
+    for (Slot &s : ret->slots)
+        if (s.state == SLOT_SCATTERING && hipEventSynchronize(s.done) != hipSuccess) return KVX_ERR_DEVICE;
+    return KVX_OK;
+}
+
+} // extern "C"

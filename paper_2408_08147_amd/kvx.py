@@ -15,7 +15,8 @@ import numpy as np
 
 from . import build as _build
 
-OK, ERR_INVALID_ARG, ERR_ALIGNMENT, ERR_BLOCK_TABLE, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_DEVICE = range(7)
+(OK, ERR_INVALID_ARG, ERR_ALIGNMENT, ERR_BLOCK_TABLE, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_DEVICE,
+ ERR_BUSY) = range(8)
 LAYOUT_LAYER_MAJOR, LAYOUT_PAGE_MAJOR = 0, 1
 INNER_TOKEN_ROWS, INNER_HEAD_MAJOR, INNER_DIM_SPLIT_TOKEN = 0, 1, 2
 OP_PACK, OP_UNPACK, OP_CONVERT = 0, 1, 2
@@ -25,6 +26,8 @@ EXPORTS = (
     "kvx_plan_segment", "kvx_plan_request_segment", "kvx_plan_get_tables", "kvx_plan_set_launch",
     "kvx_plan_get_launch", "kvx_pack", "kvx_unpack", "kvx_convert", "kvx_pack_layers",
     "kvx_unpack_layers", "kvx_convert_layers", "kvx_pack_blockwise", "kvx_copy_yardstick",
+    "kvx_retriever_arena_bytes", "kvx_retriever_create", "kvx_retriever_destroy", "kvx_retriever_acquire",
+    "kvx_retriever_scatter", "kvx_retriever_abandon", "kvx_retriever_poll", "kvx_retriever_drain",
     "kvx_status_string",
 )
 
@@ -129,9 +132,21 @@ def load():
                                       C.c_void_p]
     lib.kvx_convert_layers.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.kvx_pack_blockwise.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p]
+    lib.kvx_retriever_arena_bytes.argtypes = [C.c_uint32, C.c_uint64, C.c_uint64, C.POINTER(C.c_uint64)]
+    lib.kvx_retriever_create.argtypes = [C.c_uint32, C.c_uint64, C.c_uint64, C.c_void_p, C.c_uint64,
+                                         C.POINTER(C.c_void_p)]
+    lib.kvx_retriever_destroy.argtypes = [C.c_void_p]
+    lib.kvx_retriever_destroy.restype = None
+    lib.kvx_retriever_acquire.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.POINTER(C.c_uint32),
+                                          C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]
+    lib.kvx_retriever_scatter.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32,
+                                          C.c_void_p, C.POINTER(LaunchCfg)]
+    lib.kvx_retriever_abandon.argtypes = [C.c_void_p, C.c_uint32]
+    lib.kvx_retriever_poll.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.c_uint32, C.POINTER(C.c_uint32)]
+    lib.kvx_retriever_drain.argtypes = [C.c_void_p]
     lib.kvx_copy_yardstick.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(LaunchCfg), C.c_void_p]
     for name in EXPORTS:
-        if name not in ("kvx_status_string", "kvx_plan_destroy"):
+        if name not in ("kvx_status_string", "kvx_plan_destroy", "kvx_retriever_destroy"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -280,6 +295,74 @@ def kvx_copy_yardstick(dst: int, src: int, nbytes: int, stream: int = 0, unroll:
     cfg = LaunchCfg(unroll, nontemporal, 0, 0, max_workgroups, threads)
     _check(load().kvx_copy_yardstick(C.c_void_p(dst or None), C.c_void_p(src or None), nbytes, C.byref(cfg),
                                      C.c_void_p(stream or None)), "kvx_copy_yardstick")
+
+
+def kvx_retriever_arena_bytes(num_slots: int, slot_buf_bytes: int, slot_ws_bytes: int) -> int:
+    out = C.c_uint64(0)
+    _check(load().kvx_retriever_arena_bytes(num_slots, slot_buf_bytes, slot_ws_bytes, C.byref(out)),
+           "kvx_retriever_arena_bytes")
+    return out.value
+
+
+class Retriever:
+    """Owns a kvx_retriever_t*."""
+
+    def __init__(self, handle: int):
+        self.handle = C.c_void_p(handle)
+
+    def destroy(self) -> None:
+        if self.handle:
+            load().kvx_retriever_destroy(self.handle)
+            self.handle = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def kvx_retriever_create(num_slots: int, slot_buf_bytes: int, slot_ws_bytes: int, dev_arena: int,
+                         arena_bytes: int) -> Retriever:
+    out = C.c_void_p(None)
+    _check(load().kvx_retriever_create(num_slots, slot_buf_bytes, slot_ws_bytes, C.c_void_p(dev_arena or None),
+                                       arena_bytes, C.byref(out)), "kvx_retriever_create")
+    return Retriever(out.value)
+
+
+def kvx_retriever_destroy(ret: Retriever) -> None:
+    ret.destroy()
+
+
+def kvx_retriever_acquire(ret: Retriever, ticket: int, need_bytes: int) -> Tuple[int, int, int]:
+    """Returns (slot, slot_buf address, slot stream handle)."""
+    slot, buf, stream = C.c_uint32(0), C.c_void_p(None), C.c_void_p(None)
+    _check(load().kvx_retriever_acquire(ret.handle, ticket, need_bytes, C.byref(slot), C.byref(buf),
+                                        C.byref(stream)), "kvx_retriever_acquire")
+    return slot.value, buf.value or 0, stream.value or 0
+
+
+def kvx_retriever_scatter(ret: Retriever, slot: int, d: PoolDesc, db: BatchDesc, layer_begin: int,
+                          layer_end: int, dst_pool: int, launch: Optional[LaunchCfg] = None) -> None:
+    _check(load().kvx_retriever_scatter(ret.handle, slot, _ref(d), _ref(db), layer_begin, layer_end,
+                                        C.c_void_p(dst_pool or None), C.byref(launch) if launch else None),
+           "kvx_retriever_scatter")
+
+
+def kvx_retriever_abandon(ret: Retriever, slot: int) -> None:
+    _check(load().kvx_retriever_abandon(ret.handle, slot), "kvx_retriever_abandon")
+
+
+def kvx_retriever_poll(ret: Retriever, capacity: int = 64):
+    """Returns the list of tickets completed since they were last reported."""
+    arr = (C.c_uint64 * max(capacity, 1))()
+    n = C.c_uint32(0)
+    _check(load().kvx_retriever_poll(ret.handle, arr, capacity, C.byref(n)), "kvx_retriever_poll")
+    return [int(arr[i]) for i in range(n.value)]
+
+
+def kvx_retriever_drain(ret: Retriever) -> None:
+    _check(load().kvx_retriever_drain(ret.handle), "kvx_retriever_drain")
 
 
 def pool_desc(num_layers: int, num_kv_heads: int, head_dim: int, elem_bytes: int, page_tokens: int,

@@ -26,8 +26,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    seen = {kvx.status_string(i) for i in range(7)}
-    assert len(seen) == 7 and "ok" in seen
+    seen = {kvx.status_string(i) for i in range(8)}
+    assert len(seen) == 8 and "ok" in seen
 
 
 def _simple(n=(100, 33), P=16, NP=64):
