@@ -6,6 +6,7 @@
            against ONE planned kernel launch, over a sweep of page sizes at fixed tokens
   layers   per-layer triggers (section 3.6): the whole model in one launch, one launch per layer on the
            same plan and buffer, and the same with the grid capped to a share of the compute units
+  retrieval asynchronous retrieval (section 3.6): requests arriving one by one through k receive slots
   layouts  pools whose pages are head-major or keep the token axis inside 16-byte groups of the head
            dimension, against plain [token][head][dim] pages of the same shape
 """
@@ -112,16 +113,77 @@ def study_layouts(args):
             torch.cuda.empty_cache()
 
 
+def study_retrieval(args):
+    """Requests of the workload-5 shape arrive one by one and are scattered through k receive slots;
+    k = 1 is one transfer after another."""
+    import numpy as np
+    import torch
+    from paper_2408_08147_amd import kvx, workloads as W
+    w = W.CONFIGS[5].scaled(num_requests=args.requests)
+    b = W.draw_batch(w)
+    dev = torch.device("cuda:0")
+    L, row = w.num_layers, w.row_bytes
+    sp = kvx.pool_desc(L, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_s, b.num_pages_s, w.layout_s)
+    dp = kvx.pool_desc(L, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_d, b.num_pages_d, w.layout_d)
+    src = torch.empty(sp.dense_bytes, dtype=torch.uint8, device=dev)
+    dst = torch.empty(dp.dense_bytes, dtype=torch.uint8, device=dev)
+    reqs = []
+    for r in range(w.num_requests):
+        n = [int(b.seq_lens[r])]
+        a, z = int(b.offs_s[r]), int(b.offs_s[r + 1])
+        c, y = int(b.offs_d[r]), int(b.offs_d[r + 1])
+        reqs.append((n[0] * L * 2 * row, kvx.BatchDesc(n, b.ids_s[a:z], [0, z - a]),
+                     kvx.BatchDesc(n, b.ids_d[c:y], [0, y - c])))
+    payload = sum(x[0] for x in reqs)
+    slot_buf = max(x[0] for x in reqs)
+    for k in (1, 2, 4, 8, 16):
+        arena_bytes = kvx.kvx_retriever_arena_bytes(k, slot_buf, 1 << 16)
+        arena = torch.empty(arena_bytes, dtype=torch.uint8, device=dev)
+        send_ws = torch.empty(k, 1 << 16, dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        ret = kvx.kvx_retriever_create(k, slot_buf, 1 << 16, arena.data_ptr(), arena_bytes)
+        for timed in (False, True):
+            pending, done, polls = list(range(len(reqs))), 0, 0
+            submitted_at, latency = {}, []
+            t0 = time.perf_counter()
+            while done < len(reqs):
+                polls += 1
+                for t in kvx.kvx_retriever_poll(ret):
+                    latency.append(time.perf_counter() - submitted_at[t])
+                    done += 1
+                while pending:
+                    need, sb, db = reqs[pending[0]]
+                    try:
+                        slot, buf_ptr, stream = kvx.kvx_retriever_acquire(ret, pending[0], need)
+                    except kvx.KvxError:
+                        break
+                    submitted_at[pending.pop(0)] = time.perf_counter()
+                    plan = kvx.kvx_plan(sp, sb, None, None, 0, L, send_ws[slot].data_ptr(), 1 << 16, stream)
+                    kvx.kvx_pack(plan, src.data_ptr(), buf_ptr, slot_buf, stream)
+                    plan.destroy()
+                    kvx.kvx_retriever_scatter(ret, slot, dp, db, 0, L, dst.data_ptr())
+            kvx.kvx_retriever_drain(ret)
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t0
+        ret.destroy()
+        print(json.dumps({"study": "retrieval", "slots": k, "requests": len(reqs), "payload_bytes": payload,
+                          "total_ms": round(wall * 1e3, 3), "us_per_request": round(wall * 1e6 / len(reqs), 2),
+                          "mean_completion_us": round(1e6 * sum(latency) / len(latency), 1),
+                          "GBps_moved_pack_plus_unpack": round(2 * payload / wall / 1e9, 1)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["blocks", "layers", "layouts"])
+    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval"])
+    ap.add_argument("--requests", type=int, default=512, help="retrieval: requests of the workload-5 shape")
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 5])
     ap.add_argument("--layers", type=int, default=8, help="blocks: layers of the workload-2 shape to move")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench_studies.py: no GPU visible")
-    {"blocks": study_blocks, "layers": study_layers, "layouts": study_layouts}[args.study](args)
+    {"blocks": study_blocks, "layers": study_layers, "layouts": study_layouts,
+     "retrieval": study_retrieval}[args.study](args)
 
 
 if __name__ == "__main__":
