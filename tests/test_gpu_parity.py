@@ -247,3 +247,30 @@ def test_runtime_argument_errors():
         assert e.value.status == status
     torch.cuda.synchronize()
     plan.destroy()
+
+
+# ------------------------------------------------------------------ extreme shapes
+def test_many_tiny_requests_and_single_token_pages():
+    """40 000 requests (40 passes of the scan kernel), pages of one token, 16-byte rows."""
+    rng = np.random.default_rng(101)
+    lens = rng.integers(0, 4, size=40000).astype(np.uint32)
+    case = G.make_case(rng, 2, 1, 16, 1, lens, 1, 2, LM, PM)
+    check(case, 102)
+
+
+def test_one_very_long_request():
+    """A single request of 300 000 tokens: offsets beyond 32 bits inside one request's segment."""
+    rng = np.random.default_rng(103)
+    case = G.make_case(rng, 1, 8, 128, 2, [300000], 128, 16, LM, LM, slack_pages=0)
+    src = rng.integers(0, 256, size=case.pool_bytes(case.s), dtype=np.uint8)
+    assert case.pool_bytes(case.s) > 2 ** 31
+    want = G.run_oracle(case, src, 0, 1)
+    got = G.run_gpu(case, src, 0, 1)
+    G.assert_same(got, want, "long request")
+
+
+def test_wide_rows_and_large_pages():
+    """64 KiB rows (64 heads x 256 x 4 bytes) in pages of 512 tokens: a 32 MiB page chunk."""
+    rng = np.random.default_rng(104)
+    case = G.make_case(rng, 1, 64, 256, 4, [513, 40], 512, 256, LM, PM, slack_pages=0)
+    check(case, 105)
