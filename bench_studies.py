@@ -68,9 +68,19 @@ def study_layers(args):
     layered = s.time_op(per_layer, iters=10, warmup=2)
     one = s.time_op(lambda: kvx.kvx_pack_layers(p, 0, 1, s.src.data_ptr(), s.buf.data_ptr(), s.payload,
                                                 s.stream.cuda_stream), iters=50, warmup=5)
+    # the same 2*L launches captured once in a HIP graph and replayed
+    import torch
+    s.stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=s.stream):
+        per_layer()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s.stream):
+        graphed = s.time_op(graph.replay, iters=10, warmup=2)
     print(json.dumps({"study": "layers", "workload": w.name, "layers": L, "payload_bytes": s.payload,
                       "whole_model_pack_unpack_ms": round(whole, 4),
                       "layer_by_layer_pack_unpack_ms": round(layered, 4),
+                      "layer_by_layer_hip_graph_replay_ms": round(graphed, 4),
                       "one_layer_pack_us": round(one * 1e3, 2),
                       "one_layer_payload_bytes": s.payload // L,
                       "one_layer_hbm_GBps": round(2 * s.payload / L / one / 1e6, 1)}), flush=True)

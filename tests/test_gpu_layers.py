@@ -158,3 +158,47 @@ def test_blockwise_baseline_with_padded_rows():
     torch.cuda.synchronize()
     assert np.array_equal(buf.cpu().numpy(), want)
     plan.destroy()
+
+
+def test_layer_triggers_captured_in_a_hip_graph():
+    """The per-layer launches carry plain kernel arguments and no memset, so a whole layer-by-layer
+    transfer can be captured once and replayed; every replay, with eager work in between, must give
+    what the eager calls give on the data of that moment."""
+    import torch
+    case, src = setup_case(0, 1, 32, 16)
+    L = case.num_layers
+    dev = torch.device("cuda:0")
+    st = torch.cuda.Stream(device=dev)
+    sp, dp = case.kvx_pool(case.s), case.kvx_pool(case.d)
+    sb = kvx.BatchDesc(case.seq_lens, case.ids_s, case.offs_s)
+    db = kvx.BatchDesc(case.seq_lens, case.ids_d, case.offs_d)
+    nws = kvx.kvx_plan_workspace_bytes(sp, sb, dp, db)
+    with torch.cuda.stream(st):
+        ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+        src_t = torch.from_numpy(src).to(dev)
+        plan = kvx.kvx_plan(sp, sb, dp, db, 0, L, ws.data_ptr(), nws, st.cuda_stream)   # built eagerly, outside the graph
+        total = kvx.kvx_plan_total_bytes(plan)
+        buf = torch.full((total + G.BUF_SLACK,), G.CANARY_BUF, dtype=torch.uint8, device=dev)
+        dst = torch.full((case.pool_bytes(case.d),), G.CANARY_POOL, dtype=torch.uint8, device=dev)
+    st.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=st):
+        for l in range(L):
+            kvx.kvx_pack_layers(plan, l, l + 1, src_t.data_ptr(), buf.data_ptr(), total, st.cuda_stream)
+        for l in range(L):
+            kvx.kvx_unpack_layers(plan, l, l + 1, buf.data_ptr(), total, dst.data_ptr(), st.cuda_stream)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(55)
+    for rep in range(4):
+        # eager work between the replays: new source bytes, destination and buffer back to canaries
+        new_src = rng.integers(0, 256, size=src.size, dtype=np.uint8)
+        src_t.copy_(torch.from_numpy(new_src))
+        buf.fill_(G.CANARY_BUF)
+        dst.fill_(G.CANARY_POOL)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = G.run_oracle(case, new_src, 0, L)
+        assert np.array_equal(buf.cpu().numpy(), want.buf), f"replay {rep}: buffer"
+        assert np.array_equal(dst.cpu().numpy(), want.dst_unpack), f"replay {rep}: receiver pool"
+    plan.destroy()
