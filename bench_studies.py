@@ -7,6 +7,7 @@
   layers   per-layer triggers (section 3.6): the whole model in one launch, one launch per layer on the
            same plan and buffer, and the same with the grid capped to a share of the compute units
   retrieval asynchronous retrieval (section 3.6): requests arriving one by one through k receive slots
+  slice    a head slice of a wider sender pool through explicit strides (unequal tensor-parallel degrees)
   layouts  pools whose pages are head-major or keep the token axis inside 16-byte groups of the head
            dimension, against plain [token][head][dim] pages of the same shape
 """
@@ -182,9 +183,52 @@ def study_retrieval(args):
                           "GBps_moved_pack_plus_unpack": round(2 * payload / wall / 1e9, 1)}), flush=True)
 
 
+def study_slice(args):
+    """A head slice of a wider sender pool (sender with all 8 KV heads, receiver holding heads [2,6)):
+    the sender is described by explicit strides and a moved base pointer; rows are 1 KiB pieces at a
+    2 KiB pitch, so the tile kernel moves them."""
+    import torch
+    from paper_2408_08147_amd import kvx, workloads as W
+    w = W.CONFIGS[2]
+    b = W.draw_batch(w)
+    dev = torch.device("cuda:0")
+    st = torch.cuda.Stream(device=dev)
+    L, D, e, P = w.num_layers, w.head_dim, w.elem_bytes, w.page_s
+    h0, h1, H_full = 2, 6, w.num_kv_heads
+    row_full = H_full * D * e
+    st_page = P * row_full
+    st_kv = b.num_pages_s * st_page
+    st_layer = 2 * st_kv
+    sp = kvx.pool_desc(L, h1 - h0, D, e, P, b.num_pages_s, 0, (st_layer, st_kv, st_page, row_full))
+    dp = kvx.pool_desc(L, h1 - h0, D, e, w.page_d, b.num_pages_d, w.layout_d)
+    sb = kvx.BatchDesc(b.seq_lens, b.ids_s, b.offs_s)
+    db = kvx.BatchDesc(b.seq_lens, b.ids_d, b.offs_d)
+    nws = kvx.kvx_plan_workspace_bytes(sp, sb, dp, db)
+    src = torch.empty(L * st_layer, dtype=torch.uint8, device=dev)
+    dst = torch.empty(dp.dense_bytes, dtype=torch.uint8, device=dev)
+    ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    plan = kvx.kvx_plan(sp, sb, dp, db, 0, L, ws.data_ptr(), nws, st.cuda_stream)
+    total = kvx.kvx_plan_total_bytes(plan)
+    buf = torch.empty(total, dtype=torch.uint8, device=dev)
+    base = src.data_ptr() + h0 * D * e
+    timer = bench.Setup.time_op
+
+    holder = type("H", (), {"torch": torch, "stream": st})()
+    tp = timer(holder, lambda: kvx.kvx_pack(plan, base, buf.data_ptr(), total, st.cuda_stream), iters=8, warmup=2)
+    tu = timer(holder, lambda: kvx.kvx_unpack(plan, buf.data_ptr(), total, dst.data_ptr(), st.cuda_stream), iters=8,
+               warmup=2)
+    tc = timer(holder, lambda: kvx.kvx_convert(plan, base, dst.data_ptr(), st.cuda_stream), iters=8, warmup=2)
+    plan.destroy()
+    g = lambda ms: round(2 * total / ms / 1e6, 1)
+    print(json.dumps({"study": "head_slice", "shape": "workload 2, heads [2,6) of 8", "payload_bytes": total,
+                      "piece_bytes": (h1 - h0) * D * e, "pitch_bytes": row_full,
+                      "pack_hbm_GBps": g(tp), "unpack_hbm_GBps": g(tu), "convert_hbm_GBps": g(tc)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval"])
+    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval", "slice"])
     ap.add_argument("--requests", type=int, default=512, help="retrieval: requests of the workload-5 shape")
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 5])
     ap.add_argument("--layers", type=int, default=8, help="blocks: layers of the workload-2 shape to move")
@@ -193,7 +237,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench_studies.py: no GPU visible")
     {"blocks": study_blocks, "layers": study_layers, "layouts": study_layouts,
-     "retrieval": study_retrieval}[args.study](args)
+     "retrieval": study_retrieval, "slice": study_slice}[args.study](args)
 
 
 if __name__ == "__main__":

@@ -23,6 +23,7 @@ struct Geometry {
     uint64_t row = 0;
     uint64_t sl = 0, sk = 0, sp = 0, st = 0; // resolved byte strides
     bool custom_strides = false;
+    bool dense_rows = true;                  // [token][head][dim] with rows back to back
     uint32_t quantum = 0;                    // tokens that form one affine span inside a page
     // 16-byte unit u of the token in slot s sits at s*token_step + (u/upg)*granule_step + (u%upg)*16
     uint64_t token_step = 0, granule_step = 0;
@@ -95,7 +96,6 @@ kvx_status resolve_pool(const kvx_pool_desc *d, Geometry *g) {
         if (any) return KVX_ERR_INVALID_ARG;
         if (head_bytes % 16) return KVX_ERR_ALIGNMENT;
         if (d->inner == KVX_INNER_DIM_SPLIT_TOKEN && 16 % d->elem_bytes) return KVX_ERR_INVALID_ARG;
-        if (row / 16 >= 65536) return KVX_ERR_UNSUPPORTED;
     }
     if (any) {
         if (!d->stride_layer || !d->stride_kv || !d->stride_page || !d->stride_token)
@@ -121,7 +121,11 @@ kvx_status resolve_pool(const kvx_pool_desc *d, Geometry *g) {
     } else {
         return KVX_ERR_INVALID_ARG;
     }
-    g->quantum = (g->st == row) ? d->page_tokens : 1u;
+    // Inside a page every arrangement is affine in the slot, so a run may span a whole page; only pages
+    // whose rows are back to back can be moved as flat bytes, the others go through the tile kernel.
+    g->quantum = d->page_tokens;
+    g->dense_rows = (d->inner == KVX_INNER_TOKEN_ROWS && g->st == row);
+    if (!g->dense_rows && row / 16 >= 65536) return KVX_ERR_UNSUPPORTED;
     g->token_step = g->st;
     g->upg = (uint32_t)(row / 16);
     if (d->inner == KVX_INNER_HEAD_MAJOR) {
@@ -611,7 +615,7 @@ kvx_status run_xpose(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, co
     xp.total_tiles = (uint32_t)total;
     xp.order = c.order;
     if (!xp.order)
-        xp.order = (op != OP_PACK && plan->d.desc.layout == KVX_LAYOUT_PAGE_MAJOR) ? 2 : 1;
+        xp.order = (op != OP_PACK && !plan->d.custom_strides && plan->d.desc.layout == KVX_LAYOUT_PAGE_MAJOR) ? 2 : 1;
     xp.group = o.group_slots;
     const uint32_t grid_cap = std::min<uint32_t>(c.max_workgroups, (1u << 31) / kXposeThreads - 8u);
     uint32_t grid = std::min(xp.total_tiles, grid_cap);
@@ -634,8 +638,8 @@ kvx_status run_op(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, const
     if (!src || !dst) return KVX_ERR_INVALID_ARG;
     if (((uintptr_t)src | (uintptr_t)dst) % 16) return KVX_ERR_ALIGNMENT;
     const kvx_launch_cfg &c = plan->launch;
-    const bool src_rows = (op == OP_UNPACK) || plan->s.desc.inner == KVX_INNER_TOKEN_ROWS;
-    const bool dst_rows = (op == OP_PACK) || plan->d.desc.inner == KVX_INNER_TOKEN_ROWS;
+    const bool src_rows = (op == OP_UNPACK) || plan->s.dense_rows;
+    const bool dst_rows = (op == OP_PACK) || plan->d.dense_rows;
     if (!src_rows || !dst_rows) return run_xpose(plan, op, lb, le, src, dst, stream);
     CopyParams cp{};
     cp.runs = reinterpret_cast<const kvx_run *>(plan->ws + plan->z.off_runs[op]);

@@ -274,3 +274,39 @@ def test_wide_rows_and_large_pages():
     rng = np.random.default_rng(104)
     case = G.make_case(rng, 1, 64, 256, 4, [513, 40], 512, 256, LM, PM, slack_pages=0)
     check(case, 105)
+
+
+def test_head_slice_through_explicit_strides():
+    """A slice of the heads of a wider pool (unequal tensor-parallel degrees between the sides): the
+    pool is described with the slice's head count, the full pool's strides, and a base pointer moved to
+    the first head of the slice."""
+    rng = np.random.default_rng(106)
+    L, H_full, D, e, Ps, Pd = 2, 8, 64, 2, 16, 8
+    h0, h1 = 2, 5
+    row_full = H_full * D * e
+    lens = np.array([100, 7, 0, 260, 33], dtype=np.uint32)
+    nps = 2 * int(sum((int(n) + Ps - 1) // Ps for n in lens)) + 1
+    st_page = Ps * row_full
+    st_kv = nps * st_page
+    st_layer = 2 * st_kv
+    full_bytes = L * st_layer
+    off = h0 * D * e
+    s = G.Side(Ps, nps, 0, (st_layer, st_kv, st_page, row_full), full_bytes - off)
+    npd = 2 * int(sum((int(n) + Pd - 1) // Pd for n in lens)) + 1
+    d = G.Side(Pd, npd, 1)                                            # the receiver holds just the slice, densely
+    ids_s, offs_s = G.tables(rng, lens, Ps, nps)
+    ids_d, offs_d = G.tables(rng, lens, Pd, npd)
+    case = G.Case(L, h1 - h0, D, e, lens, s, d, ids_s, offs_s, ids_d, offs_d)
+    full = rng.integers(0, 256, size=full_bytes, dtype=np.uint8)
+    src = np.ascontiguousarray(full[off:])
+    want = G.run_oracle(case, src, 0, L)
+    got = G.run_gpu(case, src, 0, L)
+    G.assert_same(got, want, "head slice")
+    # and the slice really is heads [h0,h1) of every token: check one row against the full pool by hand
+    r, t = 3, 41
+    page = int(ids_s[int(offs_s[r]) + t // Ps])
+    row = full[0 * st_layer + 1 * st_kv + page * st_page + (t % Ps) * row_full:][:row_full]
+    T_r = int(lens[:r].sum())
+    slice_row = (h1 - h0) * D * e
+    o = T_r * L * 2 * slice_row + ((0 * 2 + 1) * int(lens[r]) + t) * slice_row
+    assert np.array_equal(got.buf[o:o + slice_row], row[off:off + slice_row])
