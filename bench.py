@@ -24,21 +24,20 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per copy_kernel launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by the plain-copy calibration), valid only for the kernel source they were taken on.
 COUNTER_RUNS = {
-    2: {"kernels_sha256": "b1aba360623ee34871f620ba867da6fb4c98625125cc6c902bef8d8a53ac6c9a",
-        "traffic_bytes_per_launch": 12099303556},
+    "kernels_sha256": "c648762770d5a887b4ca3285ba356e296d978bfff24ea68550b90dd4941a8545",
+    "traffic_bytes_per_launch": {2: 12099546599, 3: 13224616507, 5: 46982643962, 4: 152923019018},
 }
 
 
 def measured_traffic(workload: int):
     import hashlib
-    rec = COUNTER_RUNS.get(workload)
-    if not rec:
+    if workload not in COUNTER_RUNS["traffic_bytes_per_launch"]:
         return None
     src = os.path.join(ROOT, "paper_2408_08147_amd", "csrc", "kvx_kernels.hip")
     with open(src, "rb") as f:
-        if hashlib.sha256(f.read()).hexdigest() != rec["kernels_sha256"]:
+        if hashlib.sha256(f.read()).hexdigest() != COUNTER_RUNS["kernels_sha256"]:
             return None  # the kernel changed since the counters were taken
-    return rec["traffic_bytes_per_launch"]
+    return COUNTER_RUNS["traffic_bytes_per_launch"][workload]
 
 
 class Setup:
