@@ -106,16 +106,16 @@ def test_workload_2_full_every_layer():
     run_fullsize(2, list(range(32)), ("pack", "unpack"))
 
 
-def test_workload_3_full_sampled_layers():
-    run_fullsize(3, [0, 1, 17, 40, 63, 78, 79], ("pack", "unpack"))
+def test_workload_3_full_every_layer():
+    run_fullsize(3, list(range(80)), ("pack", "unpack"))
 
 
 def test_workload_5_full_sampled_layers():
-    run_fullsize(5, [0, 13, 26, 39], ("pack", "unpack"))
+    run_fullsize(5, list(range(0, 40, 2)), ("pack", "unpack"))
 
 
 def test_workload_4_full_convert_sampled_layers():
-    run_fullsize(4, [0, 19, 39], ("convert",))
+    run_fullsize(4, [0, 1, 5, 9, 13, 17, 19, 23, 26, 31, 35, 39], ("convert",))
 
 
 def test_workload_2_full_convert():
