@@ -7,6 +7,7 @@
   layers   per-layer triggers (section 3.6): the whole model in one launch, one launch per layer on the
            same plan and buffer, and the same with the grid capped to a share of the compute units
   retrieval asynchronous retrieval (section 3.6): requests arriving one by one through k receive slots
+  overlap  RecvScatter beside a stand-in for the running model (GEMMs on another stream), grid capped or not
   slice    a head slice of a wider sender pool through explicit strides (unequal tensor-parallel degrees)
   layouts  pools whose pages are head-major or keep the token axis inside 16-byte groups of the head
            dimension, against plain [token][head][dim] pages of the same shape
@@ -183,6 +184,62 @@ def study_retrieval(args):
                           "GBps_moved_pack_plus_unpack": round(2 * payload / wall / 1e9, 1)}), flush=True)
 
 
+def study_overlap(args):
+    """RecvScatter beside a running model (section 3.6: the operator form must not interrupt the other
+    operators; retrieval does no harm to the running requests): a stand-in for decoding (bf16 GEMMs from
+    torch on one stream) runs alone, then with unpacks of workload 2 in a loop on another stream, with the
+    transfer's grid uncapped and capped."""
+    import torch
+    s = bench.Setup(args.workload)
+    kvx = s.kvx
+    p = s.plan()
+    s.pack(p)
+    s.stream.synchronize()
+    a = torch.randn(8192, 8192, device=s.dev, dtype=torch.bfloat16)
+    b = torch.randn(8192, 8192, device=s.dev, dtype=torch.bfloat16)
+    model_stream = torch.cuda.Stream(device=s.dev)
+    flops = 2 * 8192 ** 3
+    reps = 40
+
+    def gemms():
+        with torch.cuda.stream(model_stream):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(model_stream)
+            for _ in range(reps):
+                torch.matmul(a, b)
+            e1.record(model_stream)
+        return e0, e1
+
+    e0, e1 = gemms()
+    e1.synchronize()
+    e0, e1 = gemms()
+    e1.synchronize()
+    alone_ms = e0.elapsed_time(e1) / reps
+    t_alone = s.time_op(lambda: s.unpack(p), iters=10, warmup=2)
+    print(json.dumps({"study": "overlap", "case": "each alone", "gemm_ms": round(alone_ms, 4),
+                      "gemm_TFLOPs": round(flops / alone_ms / 1e9, 1), "unpack_ms": round(t_alone, 4),
+                      "unpack_hbm_GBps": round(2 * s.payload / t_alone / 1e6, 1)}), flush=True)
+    for cap in (0, 2048, 512, 256, 128):
+        kvx.kvx_plan_set_launch(p, max_workgroups=cap)
+        n_unpacks = 30
+        t0 = torch.cuda.Event(enable_timing=True)
+        t1 = torch.cuda.Event(enable_timing=True)
+        t0.record(s.stream)
+        for _ in range(n_unpacks):
+            s.unpack(p)
+        t1.record(s.stream)
+        e0, e1 = gemms()
+        e1.synchronize()
+        t1.synchronize()
+        both_gemm = e0.elapsed_time(e1) / reps
+        both_unpack = t0.elapsed_time(t1) / n_unpacks
+        print(json.dumps({"study": "overlap", "case": "together", "transfer_max_workgroups": cap or "uncapped",
+                          "gemm_ms": round(both_gemm, 4), "gemm_slowdown": round(both_gemm / alone_ms, 3),
+                          "unpack_ms": round(both_unpack, 4),
+                          "unpack_hbm_GBps": round(2 * s.payload / both_unpack / 1e6, 1)}), flush=True)
+    p.destroy()
+
+
 def study_slice(args):
     """A head slice of a wider sender pool (sender with all 8 KV heads, receiver holding heads [2,6)):
     the sender is described by explicit strides and a moved base pointer; rows are 1 KiB pieces at a
@@ -228,7 +285,7 @@ def study_slice(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval", "slice"])
+    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval", "slice", "overlap"])
     ap.add_argument("--requests", type=int, default=512, help="retrieval: requests of the workload-5 shape")
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 5])
     ap.add_argument("--layers", type=int, default=8, help="blocks: layers of the workload-2 shape to move")
@@ -237,7 +294,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench_studies.py: no GPU visible")
     {"blocks": study_blocks, "layers": study_layers, "layouts": study_layouts,
-     "retrieval": study_retrieval, "slice": study_slice}[args.study](args)
+     "retrieval": study_retrieval, "slice": study_slice, "overlap": study_overlap}[args.study](args)
 
 
 if __name__ == "__main__":
