@@ -6,19 +6,22 @@
 //                a single workgroup.  These are the offsets section 3.6 of the
 //                paper derives from prompt length, hidden size and precision.
 //   fill_kernel  writes the flat copy plan: one kvx_run per maximal span of
-//                tokens that is contiguous on both sides of an operation.  For
+//                tokens that stays inside one page on both sides of an
+//                operation.  For
 //                convert the runs are laid out in groups of a fixed number of
 //                slots, one group per page of the coarser side, so that the
 //                data mover can keep a group together.
-//   copy_kernel  the pack / unpack / convert data mover: every workgroup takes
-//                tiles of (run, layer, K|V) and moves them with 16-byte loads
-//                and stores, all loads of a tile in flight before its first
-//                store.  No LDS: with token rows contiguous on both sides no
-//                byte changes its position inside a 16-byte unit.
-//   xpose_kernel the same three operations when a pool's pages are not
-//                [token][head][dim] inside: tiles of tokens x 16-byte units,
-//                staged through LDS when one side is contiguous along the row
-//                and the other along the tokens.
+//   copy_kernel  the pack / unpack / convert data mover for pages that are
+//                [token][head][dim] with rows back to back (a run is then one
+//                flat byte range on both sides): every workgroup takes tiles
+//                of (run, layer, K|V) and moves them with 16-byte loads and
+//                stores, all loads of a tile in flight before its first store.
+//                No LDS: no byte changes its position inside a 16-byte unit.
+//   xpose_kernel the same three operations for every other page arrangement
+//                (head-major, token axis inside 16-byte dim groups, padded or
+//                sliced rows): tiles of tokens x 16-byte units, staged through
+//                LDS when one side is contiguous along the row and the other
+//                along the tokens.
 #include <algorithm>
 
 #include "kvx_internal.h"
