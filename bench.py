@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per copy_kernel launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by the plain-copy calibration), valid only for the kernel source they were taken on.
 COUNTER_RUNS = {
-    "kernels_sha256": "e8b2a9c0f6e0830f16d04b10862f9d1e00fcd740a86e1252154089f42340754b",
-    "traffic_bytes_per_launch": {2: 12099367795, 3: 13224721057, 5: 46981836983, 4: 152924564332},
+    "kernels_sha256": "aa26cafcf9422eff4ada2e3a563a65f88a5d6fe53ac60ea8db3addab7fcd6fad",
+    "traffic_bytes_per_launch": {2: 12099264035, 3: 13224574469, 5: 46981556968, 4: 152921228983},
 }
 
 

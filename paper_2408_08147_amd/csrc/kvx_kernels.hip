@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanParams p) {
             for (int op = 0; op < (int)NUM_OPS; ++op)
                 v[SCAN_RUNS0 + op] = p.planned[op] ? count_runs(n, p.qa[op], p.qb[op], p.lcm[op]) : 0;
             if (p.planned[OP_CONVERT]) // slots, not runs: a fixed number per group
-                v[SCAN_RUNS0 + OP_CONVERT] = (n + p.group_quantum - 1) / p.group_quantum * p.group_slots;
+                v[(int)SCAN_RUNS0 + (int)OP_CONVERT] = (n + p.group_quantum - 1) / p.group_quantum * p.group_slots;
         }
         uint64_t inc[kNumScans];
 #pragma unroll
