@@ -183,3 +183,17 @@ def test_totals_and_segments_match_oracle_on_the_five_workloads(idx):
             assert kvx.kvx_plan_request_segment(p, r) == (off0, offn + lenn - off0)
         p.destroy()
     assert kvx.kvx_plan_workspace_bytes(s, sb, d, db) % 256 == 0
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/kvx.h must be usable from C99 and from C++ without any other header of this library."""
+    import subprocess
+    src = tmp_path / "use_kvx.c"
+    src.write_text('#include "kvx.h"\nint main(void) { kvx_pool_desc d; kvx_launch_cfg c; (void)d; (void)c; '
+                   'return (int)sizeof(kvx_run) - 32; }\n')
+    inc = os.path.join(ROOT, "include")
+    for cmd in (["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(src)],
+                ["g++", "-std=c++17", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++",
+                 "-I", inc, str(src)]):
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        assert res.returncode == 0, res.stderr
