@@ -133,12 +133,13 @@ typedef struct {
 typedef struct kvx_plan_s kvx_plan_t;
 
 /* One record of the flat copy plan in the device workspace: a maximal span of
- * tokens of one request that is contiguous on both sides.  The same record
+ * tokens of one request that lies in one page on both sides.  The same record
  * serves every (layer, kv) of the plan's range.  The convert table keeps a
  * fixed number of slots per page of the coarser side; a slot no run claims has
  * bytes == 0. */
 typedef struct {
-    uint64_t src_off; /* pool side: page*stride_page + slot*stride_token; buffer side: T_r*bpt + t*row */
+    uint64_t src_off; /* pool side: page*stride_page + slot*(byte step between tokens of that page
+                         arrangement); buffer side: T_r*bpt + t*row */
     uint64_t dst_off; /* likewise for the destination */
     uint32_t bytes;   /* tokens in the run * row */
     uint32_t seq_len; /* n_r of the owning request */
@@ -158,7 +159,8 @@ typedef struct {
 
 /* Bytes of device workspace kvx_plan needs for these inputs.  `s`/`sb` describe
  * the sender side, `d`/`db` the receiver side; either pair may be NULL (then
- * only pack, or only unpack, can be planned).  Validates sizes only. */
+ * only pack, or only unpack, can be planned).  Checks geometry and that the
+ * block tables cover the lengths; the remaining checks are kvx_plan's. */
 kvx_status kvx_plan_workspace_bytes(const kvx_pool_desc *s, const kvx_batch_desc *sb,
                                     const kvx_pool_desc *d, const kvx_batch_desc *db,
                                     size_t *out_bytes);
