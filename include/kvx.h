@@ -61,7 +61,7 @@ typedef enum {
                                 listed twice, CSR offsets not ascending */
     KVX_ERR_CAPACITY = 4,    /* buffer or workspace too small */
     KVX_ERR_UNSUPPORTED = 5, /* a size beyond what the kernels index (see kvx_plan) */
-    KVX_ERR_DEVICE = 6,      /* a HIP call failed; hipGetLastError has the detail */
+    KVX_ERR_DEVICE = 6,      /* a HIP call failed; kvx_last_device_error has the detail */
     KVX_ERR_BUSY = 7         /* kvx_retriever_acquire: every receive slot is in flight */
 } kvx_status;
 
@@ -118,7 +118,9 @@ typedef struct {
 typedef struct {
     uint32_t unroll;        /* 16-byte loads in flight per lane before the first store: 1,2,4,8; 0 = chosen
                                per operation together with `threads` */
-    uint32_t nontemporal;   /* 1 = off, 2 = non-temporal loads and stores */
+    uint32_t nontemporal;   /* cache policy of the 16-byte accesses: 0 = chosen per operation, 1 = default,
+                               2 = non-temporal loads and stores, 3 = non-temporal loads with agent-scope
+                               (write-through) stores */
     uint32_t order;         /* 0 = chosen per operation from the receiver's layout, 1 = (layer,kv) outermost,
                                2 = copy run (for convert: group of runs) outermost */
     uint32_t xcd_swizzle;   /* 1 = off, 2 = give each of the 8 XCDs contiguous tiles: one eighth of the grid
@@ -321,6 +323,10 @@ kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const 
                               void *stream);
 
 const char *kvx_status_string(kvx_status st);
+
+/* The hipError_t value behind this thread's most recent KVX_ERR_DEVICE (0 if none) and, through `where`
+ * (may be NULL), a static string naming the step that failed. */
+int kvx_last_device_error(const char **where);
 
 #ifdef __cplusplus
 }

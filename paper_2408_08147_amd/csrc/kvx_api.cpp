@@ -13,6 +13,16 @@
 using namespace kvx;
 
 namespace {
+thread_local int g_last_hip_error = 0;
+thread_local const char *g_last_hip_where = "";
+} // namespace
+
+void kvx::note_device_error(hipError_t e, const char *where) {
+    g_last_hip_error = (int)e;
+    g_last_hip_where = where;
+}
+
+namespace {
 
 constexpr uint64_t kAlign = 256;
 inline uint64_t align_up(uint64_t x, uint64_t a = kAlign) { return (x + a - 1) / a * a; }
@@ -320,9 +330,9 @@ struct kvx_plan_s {
 };
 
 namespace {
-// Fields the library fills at once; order, threads and unroll stay 0 (= chosen per operation at launch).
+// Fields the library fills at once; order, threads, unroll and nontemporal stay 0 (= chosen per operation
+// at launch).
 void default_launch(kvx_launch_cfg *c) {
-    if (!c->nontemporal) c->nontemporal = 2;
     if (!c->xcd_swizzle) c->xcd_swizzle = 2;
     if (!c->max_workgroups) c->max_workgroups = 1u << 24;
 }
@@ -330,6 +340,15 @@ void default_launch(kvx_launch_cfg *c) {
 // Tile shape when the caller left it open.  Measured on MI355X: with (layer,kv) outermost the smallest
 // tile (256 lanes x 16 B) with the largest grid is fastest; with the run group outermost (page-major
 // receiver) one workgroup per whole run, up to 512 lanes x 4 x 16 B = 32 KiB, is.
+// Cache policy when the caller left it open (values as in kvx_launch_cfg, minus one for the kernels).
+// Measured on MI355X: agent-scope stores gain 1-2 % where long runs are written into a pool and on a plain
+// copy, and lose 3-8 % where the runs are short or the writes go to the buffer; non-temporal loads and
+// stores are the safe choice everywhere else.
+int resolve_policy(uint32_t nontemporal, bool writes_pool, uint32_t max_run_bytes) {
+    if (nontemporal) return (int)nontemporal - 1;
+    return (writes_pool && max_run_bytes >= 128u * 1024u) ? 2 : 1;
+}
+
 void resolve_tile(uint32_t order, uint32_t max_run_bytes, uint32_t *threads, uint32_t *unroll) {
     if (*threads && *unroll) return;
     uint32_t t = 256, u = 1;
@@ -431,7 +450,8 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
         if (workspace_bytes < z.total_bytes) { delete p; return KVX_ERR_CAPACITY; }
         p->ws = static_cast<char *>(dev_workspace);
         hipStream_t hs = static_cast<hipStream_t>(stream);
-        if (pinned_acquire((size_t)std::max<uint64_t>(z.staging_bytes, 16), &p->staging) != hipSuccess) {
+        if (!hip_ok(pinned_acquire((size_t)std::max<uint64_t>(z.staging_bytes, 16), &p->staging),
+                    "pinned staging block")) {
             delete p;
             return KVX_ERR_DEVICE;
         }
@@ -441,8 +461,8 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
         if (!ids_d.empty()) std::memcpy(h + z.off_ids_d, ids_d.data(), 4ull * ids_d.size());
         bool ok = true;
         if (z.staging_bytes)
-            ok = hipMemcpyAsync(p->ws, h, z.staging_bytes, hipMemcpyHostToDevice, hs) == hipSuccess;
-        ok = ok && hipEventRecord(p->staging.copied, hs) == hipSuccess;
+            ok = hip_ok(hipMemcpyAsync(p->ws, h, z.staging_bytes, hipMemcpyHostToDevice, hs), "copy of the tables");
+        ok = ok && hip_ok(hipEventRecord(p->staging.copied, hs), "event behind the copy");
 
         ScanParams sp{};
         sp.seq_lens = reinterpret_cast<const uint32_t *>(p->ws + z.off_lens);
@@ -490,8 +510,8 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
             fp.run_prefix[op] = sp.prefix[SCAN_RUNS0 + op];
             fp.runs[op] = reinterpret_cast<kvx_run *>(p->ws + z.off_runs[op]);
         }
-        ok = ok && launch_scan(sp, hs) == hipSuccess;
-        ok = ok && launch_fill(fp, hs) == hipSuccess;
+        ok = ok && hip_ok(launch_scan(sp, hs), "scan_kernel launch");
+        ok = ok && hip_ok(launch_fill(fp, hs), "fill_kernel launch");
         if (!ok) {
             pinned_release(p->staging);
             delete p;
@@ -551,7 +571,7 @@ kvx_status kvx_plan_set_launch(kvx_plan_t *plan, const kvx_launch_cfg *cfg) {
     default_launch(&c);
     if ((c.unroll && !valid_unroll(c.unroll)) || (c.threads && !valid_threads(c.threads)))
         return KVX_ERR_INVALID_ARG;
-    if (c.nontemporal > 2 || c.order > 2 || c.xcd_swizzle > 2 || c.workgroups_per_cu > 8)
+    if (c.nontemporal > 3 || c.order > 2 || c.xcd_swizzle > 2 || c.workgroups_per_cu > 8)
         return KVX_ERR_INVALID_ARG;
     if (c.xcd_block_tiles & (c.xcd_block_tiles - 1u) || c.xcd_block_tiles > 4096u) return KVX_ERR_INVALID_ARG;
     plan->launch = c;
@@ -623,8 +643,9 @@ kvx_status run_xpose(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, co
         grid = (grid + 7u) / 8u * 8u;
         xp.swizzle_chunk = grid / 8u;
     }
-    hipError_t e = launch_xpose(xp, src_tf, dst_tf, c.nontemporal == 2, grid, static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? KVX_OK : KVX_ERR_DEVICE;
+    hipError_t e = launch_xpose(xp, src_tf, dst_tf, resolve_policy(c.nontemporal, op != OP_PACK, o.max_run_bytes), grid,
+                                static_cast<hipStream_t>(stream));
+    return hip_ok(e, "xpose_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
 }
 
 // Launches one operation over layers [lb, le) of the plan's range.  Buffer offsets stay those of the
@@ -679,9 +700,10 @@ kvx_status run_op(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, const
         cp.swizzle_chunk = grid / 8u;
         cp.swizzle_block = c.xcd_block_tiles;
     }
-    hipError_t e = launch_copy(cp, threads, unroll, c.nontemporal == 2, grid, occupancy_lds(c.workgroups_per_cu),
+    hipError_t e = launch_copy(cp, threads, unroll, resolve_policy(c.nontemporal, op != OP_PACK, o.max_run_bytes), grid,
+                               occupancy_lds(c.workgroups_per_cu),
                                static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? KVX_OK : KVX_ERR_DEVICE;
+    return hip_ok(e, "copy_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
 }
 
 } // namespace
@@ -757,8 +779,9 @@ kvx_status kvx_pack_blockwise(const kvx_plan_t *plan, const void *src_pool, void
                     } else {
                         e = hipMemcpy2DAsync(dst + bo, row, src + so, g.st, row, tokens, hipMemcpyDeviceToDevice, hs);
                     }
-                    if (e != hipSuccess) return KVX_ERR_DEVICE;
-                    if (confirm_every && ++issued % confirm_every == 0 && hipStreamSynchronize(hs) != hipSuccess)
+                    if (!hip_ok(e, "block copy")) return KVX_ERR_DEVICE;
+                    if (confirm_every && ++issued % confirm_every == 0 &&
+                        !hip_ok(hipStreamSynchronize(hs), "wait for a block"))
                         return KVX_ERR_DEVICE;
                 }
         first_id += pages;
@@ -776,9 +799,14 @@ kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const 
     resolve_tile(1, 0, &c.threads, &c.unroll);
     if (!valid_unroll(c.unroll) || !valid_threads(c.threads)) return KVX_ERR_INVALID_ARG;
     hipError_t e = launch_plain_copy(static_cast<char *>(dst), static_cast<const char *>(src), bytes, c.threads,
-                                     c.unroll,
-                                     c.nontemporal == 2, c.max_workgroups, static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? KVX_OK : KVX_ERR_DEVICE;
+                                     c.unroll, c.nontemporal ? (int)c.nontemporal - 1 : 2, c.max_workgroups,
+                                     static_cast<hipStream_t>(stream));
+    return hip_ok(e, "plain_copy_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
+}
+
+int kvx_last_device_error(const char **where) {
+    if (where) *where = g_last_hip_where;
+    return g_last_hip_error;
 }
 
 } // extern "C"

@@ -9,6 +9,14 @@
 
 namespace kvx {
 
+// Remembers, per thread, the HIP error behind the last KVX_ERR_DEVICE and where it happened.
+void note_device_error(hipError_t e, const char *where);
+inline bool hip_ok(hipError_t e, const char *where) {
+    if (e == hipSuccess) return true;
+    note_device_error(e, where);
+    return false;
+}
+
 enum Op : uint32_t { OP_PACK = 0, OP_UNPACK = 1, OP_CONVERT = 2, NUM_OPS = 3 };
 
 // Number of prefix arrays the scan kernel produces, each uint64[R+1]:
@@ -106,7 +114,7 @@ struct XposeParams {
 constexpr uint32_t kXposeThreads = 256;
 constexpr uint32_t kXposeCells = 1024; // 16-byte units per tile (16 KiB)
 
-hipError_t launch_xpose(const XposeParams &p, bool src_token_fast, bool dst_token_fast, bool nontemporal,
+hipError_t launch_xpose(const XposeParams &p, bool src_token_fast, bool dst_token_fast, int nontemporal,
                         uint32_t grid, hipStream_t stream);
 
 inline uint32_t tile_bytes(uint32_t threads, uint32_t unroll) { return threads * 16u * unroll; }
@@ -115,7 +123,7 @@ inline bool valid_unroll(uint32_t u) { return u == 1 || u == 2 || u == 4 || u ==
 
 hipError_t launch_scan(const ScanParams &p, hipStream_t stream);
 hipError_t launch_fill(const FillParams &p, hipStream_t stream);
-hipError_t launch_copy(const CopyParams &p, uint32_t threads, uint32_t unroll, bool nontemporal, uint32_t grid,
+hipError_t launch_copy(const CopyParams &p, uint32_t threads, uint32_t unroll, int nontemporal, uint32_t grid,
                        uint32_t lds_bytes, hipStream_t stream);
 
 // LDS per compute unit on gfx950, and the unused dynamic LDS to reserve per workgroup so that at most
@@ -123,7 +131,9 @@ hipError_t launch_copy(const CopyParams &p, uint32_t threads, uint32_t unroll, b
 constexpr uint32_t kLdsPerCu = 160u * 1024u;
 inline uint32_t occupancy_lds(uint32_t per_cu) { return per_cu ? kLdsPerCu / per_cu / 1024u * 1024u : 0u; }
 
+// `nontemporal` in these three: 0 default cache policy, 1 non-temporal loads and stores,
+// 2 non-temporal loads with agent-scope (write-through) stores.
 hipError_t launch_plain_copy(char *dst, const char *src, uint64_t bytes, uint32_t threads, uint32_t unroll,
-                             bool nontemporal, uint32_t max_wg, hipStream_t stream);
+                             int nontemporal, uint32_t max_wg, hipStream_t stream);
 
 } // namespace kvx

@@ -28,14 +28,19 @@ EXPORTS = (
     "kvx_unpack_layers", "kvx_convert_layers", "kvx_pack_blockwise", "kvx_copy_yardstick",
     "kvx_retriever_arena_bytes", "kvx_retriever_create", "kvx_retriever_destroy", "kvx_retriever_acquire",
     "kvx_retriever_scatter", "kvx_retriever_abandon", "kvx_retriever_poll", "kvx_retriever_drain",
-    "kvx_status_string",
+    "kvx_status_string", "kvx_last_device_error",
 )
 
 
 class KvxError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {status_string(status)} (kvx_status {status})")
+        detail = ""
+        if status == ERR_DEVICE:
+            step = C.c_char_p(None)
+            code = load().kvx_last_device_error(C.byref(step))
+            detail = f"; hipError_t {code} at {(step.value or b'?').decode()}"
+        super().__init__(f"{where}: {status_string(status)} (kvx_status {status}){detail}")
 
 
 class PoolDesc(C.Structure):
@@ -105,11 +110,22 @@ def load():
     path = lib_path()
     if not os.path.exists(path):
         _build.build()
+    # The library must share ONE HIP runtime with whoever owns the streams and buffers it is handed.
+    # PyTorch wheels carry their own copy of the runtime under another file name: were this library loaded
+    # first, the loader would bring in the system copy for it and later PyTorch's for PyTorch, and a stream
+    # or event of one is an invalid handle in the other.  With torch imported first, the dependency of this
+    # library resolves (by soname) to the copy that is already in the process.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(path)
     for name in EXPORTS:
         getattr(lib, name)  # raises AttributeError on a missing export
     lib.kvx_status_string.restype = C.c_char_p
     lib.kvx_status_string.argtypes = [C.c_int]
+    lib.kvx_last_device_error.restype = C.c_int
+    lib.kvx_last_device_error.argtypes = [C.POINTER(C.c_char_p)]
     lib.kvx_plan_destroy.restype = None
     lib.kvx_plan_destroy.argtypes = [C.c_void_p]
     lib.kvx_plan_workspace_bytes.argtypes = [C.c_void_p] * 4 + [C.POINTER(C.c_size_t)]
@@ -146,7 +162,7 @@ def load():
     lib.kvx_retriever_drain.argtypes = [C.c_void_p]
     lib.kvx_copy_yardstick.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(LaunchCfg), C.c_void_p]
     for name in EXPORTS:
-        if name not in ("kvx_status_string", "kvx_plan_destroy", "kvx_retriever_destroy"):
+        if name not in ("kvx_status_string", "kvx_plan_destroy", "kvx_retriever_destroy", "kvx_last_device_error"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib

@@ -41,6 +41,7 @@ def test_inner_arrangements(ins, ind, H, D, e, Ps, Pd, ls, ld):
 
 
 @pytest.mark.parametrize("launch", [dict(order=1), dict(order=2), dict(xcd_swizzle=1), dict(nontemporal=1),
+                                    dict(nontemporal=2), dict(nontemporal=3), dict(nontemporal=3, order=2),
                                     dict(max_workgroups=5), dict(order=2, max_workgroups=16)])
 def test_inner_results_do_not_depend_on_launch_config(launch):
     rng = np.random.default_rng(12)
