@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per copy_kernel launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by the plain-copy calibration), valid only for the kernel source they were taken on.
 COUNTER_RUNS = {
-    "kernels_sha256": "e746c66fc209d39c414a2c2e5f78e8bf76deecbf0377d7856e62acc9d5224973",
-    "traffic_bytes_per_launch": {2: 12103921037, 3: 13228530655, 5: 47003657299, 4: 152992058415},
+    "kernels_sha256": "d85f01e72d172bb3a008fa3aff2dd219b3add9281e61c977f25ee646855acda3",
+    "traffic_bytes_per_launch": {2: 12103922138, 3: 13228534254, 5: 47003764403, 4: 152992003887},
 }
 
 

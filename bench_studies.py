@@ -9,6 +9,9 @@
   retrieval asynchronous retrieval (section 3.6): requests arriving one by one through k receive slots
   overlap  RecvScatter beside a stand-in for the running model (GEMMs on another stream), grid capped or not
   slice    a head slice of a wider sender pool through explicit strides (unequal tensor-parallel degrees)
+  ceilings the device's own limits for this kind of work, measured with two plain kernels that plan nothing:
+           a contiguous copy, and the same copy cut into chunks that random permutations scatter on the
+           source side (gather), the destination side (scatter) or both, over a sweep of chunk sizes
   layouts  pools whose pages are head-major or keep the token axis inside 16-byte groups of the head
            dimension, against plain [token][head][dim] pages of the same shape
 """
@@ -240,6 +243,53 @@ def study_overlap(args):
     p.destroy()
 
 
+def study_ceilings(args):
+    import numpy as np
+    import torch
+    from paper_2408_08147_amd import kvx
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream(device=dev)
+    nbytes = args.gib << 30
+    rng = np.random.default_rng(240808147)
+    with torch.cuda.stream(stream):
+        src = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        src.random_(0, 256)
+        dst.zero_()
+
+    def timed(fn, iters=10, warmup=2):
+        for _ in range(warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(iters):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    t = timed(lambda: kvx.kvx_copy_yardstick(dst.data_ptr(), src.data_ptr(), nbytes, stream.cuda_stream))
+    print(json.dumps({"study": "ceilings", "kernel": "plain_copy_kernel", "bytes": nbytes,
+                      "ms": round(t, 4), "hbm_GBps": round(2 * nbytes / t / 1e6, 1)}), flush=True)
+    for chunk in (4096, 8192, 16384, 32768, 65536, 131072, 262144, 1048576, 4194304):
+        n = nbytes // chunk
+        with torch.cuda.stream(stream):
+            ps = torch.from_numpy(rng.permutation(n).astype(np.uint32)).to(dev)
+            pd = torch.from_numpy(rng.permutation(n).astype(np.uint32)).to(dev)
+        row = {"study": "ceilings", "kernel": "chunk_copy_kernel", "bytes": nbytes, "chunk_bytes": chunk}
+        for name, a, b in (("identity", 0, 0), ("gather", ps.data_ptr(), 0), ("scatter", 0, pd.data_ptr()),
+                           ("both", ps.data_ptr(), pd.data_ptr())):
+            t = timed(lambda: kvx.kvx_copy_yardstick_chunks(dst.data_ptr(), src.data_ptr(), nbytes, chunk, a, b,
+                                                            stream.cuda_stream))
+            row[name + "_hbm_GBps"] = round(2 * nbytes / t / 1e6, 1)
+        # the last pass (both permutations) must have produced the permuted copy
+        stream.synchronize()
+        k = int(rng.integers(0, n))
+        lo_d, lo_s = int(pd[k]) * chunk, int(ps[k]) * chunk
+        row["spot_check_ok"] = bool(torch.equal(dst[lo_d:lo_d + chunk], src[lo_s:lo_s + chunk]))
+        print(json.dumps(row), flush=True)
+
+
 def study_slice(args):
     """A head slice of a wider sender pool (sender with all 8 KV heads, receiver holding heads [2,6)):
     the sender is described by explicit strides and a moved base pointer; rows are 1 KiB pieces at a
@@ -285,16 +335,18 @@ def study_slice(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval", "slice", "overlap"])
+    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval", "slice", "overlap", "ceilings"])
     ap.add_argument("--requests", type=int, default=512, help="retrieval: requests of the workload-5 shape")
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 5])
     ap.add_argument("--layers", type=int, default=8, help="blocks: layers of the workload-2 shape to move")
+    ap.add_argument("--gib", type=int, default=4, help="ceilings: GiB copied per launch")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench_studies.py: no GPU visible")
     {"blocks": study_blocks, "layers": study_layers, "layouts": study_layouts,
-     "retrieval": study_retrieval, "slice": study_slice, "overlap": study_overlap}[args.study](args)
+     "retrieval": study_retrieval, "slice": study_slice, "overlap": study_overlap,
+     "ceilings": study_ceilings}[args.study](args)
 
 
 if __name__ == "__main__":

@@ -322,6 +322,18 @@ kvx_status kvx_retriever_drain(kvx_retriever_t *ret);
 kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const kvx_launch_cfg *cfg,
                               void *stream);
 
+/* Second yardstick: the same copy cut into chunks that two optional permutations scatter,
+ * dst chunk dst_perm[i] <- src chunk src_perm[i] (uint32 tables [device] of bytes/chunk_bytes entries;
+ * NULL = identity).  chunk_bytes is a power of two from 4096 up and divides `bytes` (at most 32 GiB);
+ * dst and src [device] are 16-byte aligned and do not overlap.  One table lookup per 4 KiB tile and
+ * nothing else: what a copy between scattered chunks of a given size can reach on this device, whatever
+ * plans it.  The tables live on the device and are NOT checked: every entry must be below
+ * bytes/chunk_bytes, and dst_perm must not repeat an entry.
+ * Errors: KVX_ERR_INVALID_ARG (NULL buffer, chunk size), KVX_ERR_ALIGNMENT, KVX_ERR_UNSUPPORTED (too large),
+ * KVX_ERR_DEVICE. */
+kvx_status kvx_copy_yardstick_chunks(void *dst, const void *src, uint64_t bytes, uint32_t chunk_bytes,
+                                     const uint32_t *src_perm, const uint32_t *dst_perm, void *stream);
+
 const char *kvx_status_string(kvx_status st);
 
 /* The hipError_t value behind this thread's most recent KVX_ERR_DEVICE (0 if none) and, through `where`

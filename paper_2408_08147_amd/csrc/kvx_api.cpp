@@ -804,6 +804,19 @@ kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const 
     return hip_ok(e, "plain_copy_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
 }
 
+kvx_status kvx_copy_yardstick_chunks(void *dst, const void *src, uint64_t bytes, uint32_t chunk_bytes,
+                                     const uint32_t *src_perm, const uint32_t *dst_perm, void *stream) {
+    if (!dst || !src || chunk_bytes < 4096 || (chunk_bytes & (chunk_bytes - 1)) || bytes % chunk_bytes)
+        return KVX_ERR_INVALID_ARG;
+    if (((uintptr_t)dst | (uintptr_t)src) % 16) return KVX_ERR_ALIGNMENT;
+    if (bytes / 4096 >= (1ull << 31) / 256) return KVX_ERR_UNSUPPORTED; // one tile per workgroup, no loop
+    uint32_t lg = 0;
+    while ((4096u << lg) < chunk_bytes) ++lg;
+    hipError_t e = launch_chunk_copy(static_cast<char *>(dst), static_cast<const char *>(src), bytes, lg, src_perm,
+                                     dst_perm, static_cast<hipStream_t>(stream));
+    return hip_ok(e, "chunk_copy_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
+}
+
 int kvx_last_device_error(const char **where) {
     if (where) *where = g_last_hip_where;
     return g_last_hip_error;

@@ -398,6 +398,23 @@ __global__ __launch_bounds__(T) void plain_copy_kernel(const char *__restrict__ 
     }
 }
 
+// Second yardstick: chunk-permuted copy, one 4 KiB tile per workgroup, the data mover's default shape.
+__global__ __launch_bounds__(256) void chunk_copy_kernel(const uint32_t *__restrict__ src_perm,
+                                                         const uint32_t *__restrict__ dst_perm,
+                                                         const char *__restrict__ src, char *__restrict__ dst,
+                                                         uint32_t log2_tiles_per_chunk, uint32_t total_tiles,
+                                                         uint32_t swizzle_chunk) {
+    const uint32_t b = (blockIdx.x & 7u) * swizzle_chunk + (blockIdx.x >> 3);
+    if (b >= total_tiles) return;
+    const uint32_t chunk = b >> log2_tiles_per_chunk;
+    const uint32_t within = b & ((1u << log2_tiles_per_chunk) - 1u);
+    const uint64_t chunk_bytes = 4096ull << log2_tiles_per_chunk;
+    const uint64_t s_chunk = src_perm ? src_perm[chunk] : chunk;
+    const uint64_t d_chunk = dst_perm ? dst_perm[chunk] : chunk;
+    const uint64_t off = within * 4096ull + threadIdx.x * 16u;
+    st16<1>(dst + d_chunk * chunk_bytes + off, ld16<1>(src + s_chunk * chunk_bytes + off));
+}
+
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
@@ -519,6 +536,16 @@ hipError_t launch_xpose(const XposeParams &p, bool src_token_fast, bool dst_toke
                               : xpose_sd<true, false>(p, nontemporal, grid, stream);
     return dst_token_fast ? xpose_sd<false, true>(p, nontemporal, grid, stream)
                           : xpose_sd<false, false>(p, nontemporal, grid, stream);
+}
+
+hipError_t launch_chunk_copy(char *dst, const char *src, uint64_t bytes, uint32_t log2_tiles_per_chunk,
+                             const uint32_t *src_perm, const uint32_t *dst_perm, hipStream_t stream) {
+    const uint32_t tiles = (uint32_t)(bytes / 4096);
+    if (tiles == 0) return hipSuccess;
+    const uint32_t grid = (tiles + 7u) / 8u * 8u;
+    KVX_LAUNCH(chunk_copy_kernel, dim3(grid), dim3(256), 0, stream, src_perm, dst_perm, src, dst,
+               log2_tiles_per_chunk, tiles, grid / 8u);
+    return hipGetLastError();
 }
 
 hipError_t launch_plain_copy(char *dst, const char *src, uint64_t bytes, uint32_t threads, uint32_t unroll,

@@ -28,7 +28,7 @@ EXPORTS = (
     "kvx_unpack_layers", "kvx_convert_layers", "kvx_pack_blockwise", "kvx_copy_yardstick",
     "kvx_retriever_arena_bytes", "kvx_retriever_create", "kvx_retriever_destroy", "kvx_retriever_acquire",
     "kvx_retriever_scatter", "kvx_retriever_abandon", "kvx_retriever_poll", "kvx_retriever_drain",
-    "kvx_status_string", "kvx_last_device_error",
+    "kvx_copy_yardstick_chunks", "kvx_status_string", "kvx_last_device_error",
 )
 
 
@@ -160,6 +160,8 @@ def load():
     lib.kvx_retriever_abandon.argtypes = [C.c_void_p, C.c_uint32]
     lib.kvx_retriever_poll.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.c_uint32, C.POINTER(C.c_uint32)]
     lib.kvx_retriever_drain.argtypes = [C.c_void_p]
+    lib.kvx_copy_yardstick_chunks.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p,
+                                              C.c_void_p, C.c_void_p]
     lib.kvx_copy_yardstick.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(LaunchCfg), C.c_void_p]
     for name in EXPORTS:
         if name not in ("kvx_status_string", "kvx_plan_destroy", "kvx_retriever_destroy", "kvx_last_device_error"):
@@ -379,6 +381,13 @@ def kvx_retriever_poll(ret: Retriever, capacity: int = 64):
 
 def kvx_retriever_drain(ret: Retriever) -> None:
     _check(load().kvx_retriever_drain(ret.handle), "kvx_retriever_drain")
+
+
+def kvx_copy_yardstick_chunks(dst: int, src: int, nbytes: int, chunk_bytes: int, src_perm: int = 0,
+                              dst_perm: int = 0, stream: int = 0) -> None:
+    _check(load().kvx_copy_yardstick_chunks(C.c_void_p(dst or None), C.c_void_p(src or None), nbytes, chunk_bytes,
+                                            C.c_void_p(src_perm or None), C.c_void_p(dst_perm or None),
+                                            C.c_void_p(stream or None)), "kvx_copy_yardstick_chunks")
 
 
 def pool_desc(num_layers: int, num_kv_heads: int, head_dim: int, elem_bytes: int, page_tokens: int,
