@@ -271,6 +271,10 @@ def study_ceilings(args):
     t = timed(lambda: kvx.kvx_copy_yardstick(dst.data_ptr(), src.data_ptr(), nbytes, stream.cuda_stream))
     print(json.dumps({"study": "ceilings", "kernel": "plain_copy_kernel", "bytes": nbytes,
                       "ms": round(t, 4), "hbm_GBps": round(2 * nbytes / t / 1e6, 1)}), flush=True)
+    with torch.cuda.stream(stream):
+        t = timed(lambda: dst.copy_(src))
+    print(json.dumps({"study": "ceilings", "kernel": "runtime device-to-device copy (torch copy_)", "bytes": nbytes,
+                      "ms": round(t, 4), "hbm_GBps": round(2 * nbytes / t / 1e6, 1)}), flush=True)
     for chunk in (4096, 8192, 16384, 32768, 65536, 131072, 262144, 1048576, 4194304):
         n = nbytes // chunk
         with torch.cuda.stream(stream):
