@@ -62,7 +62,8 @@ typedef enum {
     KVX_ERR_CAPACITY = 4,    /* buffer or workspace too small */
     KVX_ERR_UNSUPPORTED = 5, /* a size beyond what the kernels index (see kvx_plan) */
     KVX_ERR_DEVICE = 6,      /* a HIP call failed; kvx_last_device_error has the detail */
-    KVX_ERR_BUSY = 7         /* kvx_retriever_acquire: every receive slot is in flight */
+    KVX_ERR_BUSY = 7,        /* kvx_retriever_acquire: every receive slot is in flight */
+    KVX_ERR_HOST_MEMORY = 8  /* the library's own host-side tables could not be allocated */
 } kvx_status;
 
 typedef enum {
@@ -278,6 +279,7 @@ kvx_status kvx_pack_blockwise(const kvx_plan_t *plan, const void *src_pool, void
  * Calls on one retriever must come from one thread at a time. */
 typedef struct kvx_retriever_s kvx_retriever_t;
 
+/* At most 1024 slots, each part below 2^48 bytes (KVX_ERR_UNSUPPORTED beyond). */
 kvx_status kvx_retriever_arena_bytes(uint32_t num_slots, uint64_t slot_buf_bytes, uint64_t slot_ws_bytes,
                                      uint64_t *out_bytes);
 kvx_status kvx_retriever_create(uint32_t num_slots, uint64_t slot_buf_bytes, uint64_t slot_ws_bytes,

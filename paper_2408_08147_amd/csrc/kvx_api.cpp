@@ -3,6 +3,7 @@
 // (paper section 3.6, "Block-free D2D KVCache Transfer").
 #include <algorithm>
 #include <cstring>
+#include <memory>
 #include <mutex>
 #include <new>
 #include <numeric>
@@ -373,6 +374,7 @@ const char *kvx_status_string(kvx_status st) {
     case KVX_ERR_UNSUPPORTED: return "size not supported";
     case KVX_ERR_DEVICE: return "HIP error";
     case KVX_ERR_BUSY: return "every receive slot is in flight";
+    case KVX_ERR_HOST_MEMORY: return "out of host memory";
     }
     return "unknown status";
 }
@@ -399,26 +401,23 @@ kvx_status kvx_plan_workspace_bytes(const kvx_pool_desc *s, const kvx_batch_desc
 kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_pool_desc *d,
                     const kvx_batch_desc *db, uint32_t layer_begin, uint32_t layer_end,
                     void *dev_workspace, size_t workspace_bytes, void *stream,
-                    kvx_plan_t **out_plan) {
+                    kvx_plan_t **out_plan) try {
     if (!out_plan) return KVX_ERR_INVALID_ARG;
     *out_plan = nullptr;
-    kvx_plan_s *p = new (std::nothrow) kvx_plan_s;
-    if (!p) return KVX_ERR_INVALID_ARG;
+    std::unique_ptr<kvx_plan_s> owner(new kvx_plan_s);
+    kvx_plan_s *p = owner.get();
     kvx_status st = check_sides(s, sb, d, db, &p->s, &p->d);
-    if (st != KVX_OK) { delete p; return st; }
-    if (layer_begin > layer_end || (s && layer_end > s->num_layers) || (d && layer_end > d->num_layers)) {
-        delete p;
-        return KVX_ERR_INVALID_ARG;
-    }
-    if ((dev_workspace == nullptr) != (workspace_bytes == 0)) { delete p; return KVX_ERR_INVALID_ARG; }
-    if ((uintptr_t)dev_workspace % kAlign) { delete p; return KVX_ERR_ALIGNMENT; }
+    if (st != KVX_OK) return st;
+    if (layer_begin > layer_end || (s && layer_end > s->num_layers) || (d && layer_end > d->num_layers)) return KVX_ERR_INVALID_ARG;
+    if ((dev_workspace == nullptr) != (workspace_bytes == 0)) return KVX_ERR_INVALID_ARG;
+    if ((uintptr_t)dev_workspace % kAlign) return KVX_ERR_ALIGNMENT;
 
     const kvx_batch_desc *b = sb ? sb : db;
     const uint32_t R = b->num_requests;
     std::vector<uint32_t> &ids_s = p->ids_s;
     std::vector<uint32_t> ids_d;
-    if (s && (st = check_tables(p->s, sb, false, &ids_s, &p->s.used_pages)) != KVX_OK) { delete p; return st; }
-    if (d && (st = check_tables(p->d, db, true, &ids_d, &p->d.used_pages)) != KVX_OK) { delete p; return st; }
+    if (s && (st = check_tables(p->s, sb, false, &ids_s, &p->s.used_pages)) != KVX_OK) return st;
+    if (d && (st = check_tables(p->d, db, true, &ids_d, &p->d.used_pages)) != KVX_OK) return st;
 
     p->R = R;
     p->l0 = layer_begin;
@@ -440,21 +439,15 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
     for (int op = 0; op < (int)NUM_OPS; ++op) {
         // even the smallest tile (one 16-byte load per lane) must give a 32-bit tile count
         const uint64_t tpr = (z.ops[op].max_run_bytes + tile_bytes(64, 1) - 1) / tile_bytes(64, 1);
-        if (z.ops[op].planned && z.ops[op].num_runs * tpr * num_lc >= (1ull << 32)) {
-            delete p;
-            return KVX_ERR_UNSUPPORTED;
-        }
+        if (z.ops[op].planned && z.ops[op].num_runs * tpr * num_lc >= (1ull << 32)) return KVX_ERR_UNSUPPORTED;
     }
 
     if (dev_workspace) {
-        if (workspace_bytes < z.total_bytes) { delete p; return KVX_ERR_CAPACITY; }
+        if (workspace_bytes < z.total_bytes) return KVX_ERR_CAPACITY;
         p->ws = static_cast<char *>(dev_workspace);
         hipStream_t hs = static_cast<hipStream_t>(stream);
         if (!hip_ok(pinned_acquire((size_t)std::max<uint64_t>(z.staging_bytes, 16), &p->staging),
-                    "pinned staging block")) {
-            delete p;
-            return KVX_ERR_DEVICE;
-        }
+                    "pinned staging block")) return KVX_ERR_DEVICE;
         char *h = static_cast<char *>(p->staging.ptr);
         if (R) std::memcpy(h + z.off_lens, p->seq_lens.data(), 4ull * R);
         if (!ids_s.empty()) std::memcpy(h + z.off_ids_s, ids_s.data(), 4ull * ids_s.size());
@@ -514,12 +507,13 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
         ok = ok && hip_ok(launch_fill(fp, hs), "fill_kernel launch");
         if (!ok) {
             pinned_release(p->staging);
-            delete p;
             return KVX_ERR_DEVICE;
         }
     }
-    *out_plan = p;
+    *out_plan = owner.release();
     return KVX_OK;
+} catch (...) { // the host tables could not be allocated; nothing was enqueued yet
+    return KVX_ERR_HOST_MEMORY;
 }
 
 void kvx_plan_destroy(kvx_plan_t *plan) {

@@ -1,12 +1,12 @@
 // Receive slots for asynchronous retrieval (paper section 3.6, "Asynchronous Retrieval"): a small,
 // fixed number of in-flight transfers on the decoding side, each on a stream of its own, completion found
 // by polling events.  Host code only; the data moves through kvx_plan + kvx_unpack.
-#include <hip/hip_runtime.h>
-
 #include <new>
 #include <vector>
 
-#include "kvx.h"
+#include "kvx_internal.h"
+
+using kvx::hip_ok;
 
 namespace {
 constexpr uint64_t kAlign = 256;
@@ -34,39 +34,47 @@ extern "C" {
 kvx_status kvx_retriever_arena_bytes(uint32_t num_slots, uint64_t slot_buf_bytes, uint64_t slot_ws_bytes,
                                      uint64_t *out_bytes) {
     if (!num_slots || !slot_buf_bytes || !slot_ws_bytes || !out_bytes) return KVX_ERR_INVALID_ARG;
+    if (slot_buf_bytes > (1ull << 48) || slot_ws_bytes > (1ull << 48) || num_slots > 1024) return KVX_ERR_UNSUPPORTED;
     *out_bytes = num_slots * (align_up(slot_buf_bytes) + align_up(slot_ws_bytes));
     return KVX_OK;
 }
 
 kvx_status kvx_retriever_create(uint32_t num_slots, uint64_t slot_buf_bytes, uint64_t slot_ws_bytes,
-                                void *dev_arena, uint64_t arena_bytes, kvx_retriever_t **out) {
+                                void *dev_arena, uint64_t arena_bytes, kvx_retriever_t **out) try {
     if (!out) return KVX_ERR_INVALID_ARG;
     *out = nullptr;
     uint64_t need = 0;
     kvx_status st = kvx_retriever_arena_bytes(num_slots, slot_buf_bytes, slot_ws_bytes, &need);
     if (st != KVX_OK) return st;
-    if (!dev_arena || num_slots > 1024) return KVX_ERR_INVALID_ARG;
+    if (!dev_arena) return KVX_ERR_INVALID_ARG;
     if ((uintptr_t)dev_arena % kAlign) return KVX_ERR_ALIGNMENT;
     if (arena_bytes < need) return KVX_ERR_CAPACITY;
     kvx_retriever_s *r = new (std::nothrow) kvx_retriever_s;
-    if (!r) return KVX_ERR_INVALID_ARG;
+    if (!r) return KVX_ERR_HOST_MEMORY;
     r->buf_bytes = align_up(slot_buf_bytes);
     r->ws_bytes = align_up(slot_ws_bytes);
-    r->slots.resize(num_slots);
+    try {
+        r->slots.resize(num_slots);
+    } catch (...) {
+        delete r;
+        return KVX_ERR_HOST_MEMORY;
+    }
     char *base = static_cast<char *>(dev_arena);
     for (uint32_t i = 0; i < num_slots; ++i) {
         Slot &s = r->slots[i];
         s.buf = base + i * (r->buf_bytes + r->ws_bytes);
         s.ws = s.buf + r->buf_bytes;
         // default priority on purpose: streams of mixed priorities are not used anywhere in this library
-        if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess ||
-            hipEventCreateWithFlags(&s.done, hipEventDisableTiming) != hipSuccess) {
+        if (!hip_ok(hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking), "stream of a receive slot") ||
+            !hip_ok(hipEventCreateWithFlags(&s.done, hipEventDisableTiming), "event of a receive slot")) {
             kvx_retriever_destroy(r);
             return KVX_ERR_DEVICE;
         }
     }
     *out = r;
     return KVX_OK;
+} catch (...) {
+    return KVX_ERR_HOST_MEMORY;
 }
 
 void kvx_retriever_destroy(kvx_retriever_t *ret) {
@@ -121,7 +129,7 @@ kvx_status kvx_retriever_scatter(kvx_retriever_t *ret, uint32_t slot, const kvx_
     if (st == KVX_OK) st = kvx_unpack(plan, s.buf, ret->buf_bytes, dst_pool, s.stream);
     kvx_plan_destroy(plan); // the launch carries its arguments; the workspace stays with the slot
     if (st != KVX_OK) return st;
-    if (hipEventRecord(s.done, s.stream) != hipSuccess) return KVX_ERR_DEVICE;
+    if (!hip_ok(hipEventRecord(s.done, s.stream), "event behind a scatter")) return KVX_ERR_DEVICE;
     s.state = SLOT_SCATTERING;
     return KVX_OK;
 }
@@ -130,7 +138,7 @@ kvx_status kvx_retriever_abandon(kvx_retriever_t *ret, uint32_t slot) {
     if (!ret || slot >= ret->slots.size()) return KVX_ERR_INVALID_ARG;
     Slot &s = ret->slots[slot];
     if (s.state != SLOT_ACQUIRED) return KVX_ERR_INVALID_ARG;
-    if (hipStreamSynchronize(s.stream) != hipSuccess) return KVX_ERR_DEVICE;
+    if (!hip_ok(hipStreamSynchronize(s.stream), "wait for an abandoned slot")) return KVX_ERR_DEVICE;
     s.state = SLOT_FREE;
     return KVX_OK;
 }
@@ -138,23 +146,25 @@ kvx_status kvx_retriever_abandon(kvx_retriever_t *ret, uint32_t slot) {
 kvx_status kvx_retriever_poll(kvx_retriever_t *ret, uint64_t *tickets, uint32_t capacity, uint32_t *count) {
     if (!ret || !count || (capacity && !tickets)) return KVX_ERR_INVALID_ARG;
     uint32_t n = 0;
+    *count = 0;
     for (Slot &s : ret->slots) {
         if (n >= capacity) break;
         if (s.state != SLOT_SCATTERING) continue;
         const hipError_t e = hipEventQuery(s.done);
         if (e == hipErrorNotReady) continue;
-        if (e != hipSuccess) return KVX_ERR_DEVICE;
+        if (!hip_ok(e, "query of a slot's event")) return KVX_ERR_DEVICE; // *count already names the slots freed
         tickets[n++] = s.ticket;
         s.state = SLOT_FREE;
+        *count = n;
     }
-    *count = n;
     return KVX_OK;
 }
 
 kvx_status kvx_retriever_drain(kvx_retriever_t *ret) {
     if (!ret) return KVX_ERR_INVALID_ARG;
     for (Slot &s : ret->slots)
-        if (s.state == SLOT_SCATTERING && hipEventSynchronize(s.done) != hipSuccess) return KVX_ERR_DEVICE;
+        if (s.state == SLOT_SCATTERING && !hip_ok(hipEventSynchronize(s.done), "wait for a slot's event"))
+            return KVX_ERR_DEVICE;
     return KVX_OK;
 }
 

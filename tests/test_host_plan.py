@@ -26,8 +26,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    seen = {kvx.status_string(i) for i in range(8)}
-    assert len(seen) == 8 and "ok" in seen
+    seen = {kvx.status_string(i) for i in range(9)}
+    assert len(seen) == 9 and "ok" in seen and kvx.status_string(8) == "out of host memory"
+    assert kvx.status_string(9) == "unknown status"
 
 
 def _simple(n=(100, 33), P=16, NP=64):
@@ -198,3 +199,13 @@ def test_header_is_plain_c(tmp_path):
                  "-I", inc, str(src)]):
         res = subprocess.run(cmd, capture_output=True, text=True)
         assert res.returncode == 0, res.stderr
+
+
+def test_retriever_sizing_errors():
+    assert kvx.kvx_retriever_arena_bytes(3, 1000, 100) == 3 * (1024 + 256)
+    for args, code in (((0, 1, 1), kvx.ERR_INVALID_ARG), ((1, 0, 1), kvx.ERR_INVALID_ARG),
+                       ((1, 1, 0), kvx.ERR_INVALID_ARG), ((1025, 1, 1), kvx.ERR_UNSUPPORTED),
+                       ((1, (1 << 48) + 1, 1), kvx.ERR_UNSUPPORTED), ((1, 1, (1 << 48) + 1), kvx.ERR_UNSUPPORTED)):
+        with pytest.raises(kvx.KvxError) as ei:
+            kvx.kvx_retriever_arena_bytes(*args)
+        assert ei.value.status == code, args
