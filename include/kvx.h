@@ -18,7 +18,12 @@
  *     The library owns only the host-side plan object.  Host arrays handed to
  *     kvx_plan are copied before it returns.
  *   - pack / unpack / convert enqueue work on `stream` and return; they never
- *     synchronise and never allocate device memory.
+ *     synchronise and never allocate device memory.  Each is one kernel launch
+ *     and nothing else, so these calls (and their _layers forms) may be recorded
+ *     while `stream` is being captured into a HIP graph; the graph then needs
+ *     the plan's workspace and the pools at the same addresses on every replay.
+ *     kvx_plan itself copies from a staging block that the library reuses and
+ *     records an event, and must not be called on a capturing stream.
  *   - Every call returns a kvx_status; nothing aborts or throws.  All argument,
  *     geometry and block-table checks happen on the host inside kvx_plan, and a
  *     plan that fails leaves the workspace untouched.

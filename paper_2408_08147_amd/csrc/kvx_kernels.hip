@@ -30,16 +30,25 @@ namespace kvx {
 
 using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ uint64_t ceil_div_q(uint64_t x, uint64_t q) {
+// Lengths, page sizes and token positions are all below 2^32, so every division of the planner is a 32-bit
+// one (the 64-bit kind is a long dependent instruction sequence here, and it was most of the planner's time).
+__device__ __forceinline__ uint32_t ceil_div_q(uint32_t x, uint32_t q) {
     // q == 0 stands for an infinite quantum: only x == 0 has no multiple below it.
-    if (q == 0) return x ? 1 : 0;
-    return (x + q - 1) / q;
+    if (q == 0) return x ? 1u : 0u;
+    return x ? (x - 1u) / q + 1u : 0u;
+}
+
+// lcm(qa, qb) may not fit 32 bits; any value of 2^32 - 1 or more divides like 2^32 - 1 does, since x < 2^32.
+__device__ __forceinline__ uint32_t clamp_lcm(uint64_t l) { return l > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)l; }
+
+// Number of cut points in [0, x) at multiples of qa and of qb (l = their lcm): the rank of a run that starts at x.
+__device__ __forceinline__ uint64_t cuts_below(uint32_t x, uint32_t qa, uint32_t qb, uint32_t l) {
+    return (uint64_t)ceil_div_q(x, qa) + ceil_div_q(x, qb) - ceil_div_q(x, l);
 }
 
 // Number of maximal runs of n tokens cut at multiples of qa and of qb.
-__device__ __forceinline__ uint64_t count_runs(uint64_t n, uint32_t qa, uint32_t qb, uint64_t l) {
-    if (n == 0) return 0;
-    return ceil_div_q(n, qa) + ceil_div_q(n, qb) - ceil_div_q(n, l);
+__device__ __forceinline__ uint64_t count_runs(uint32_t n, uint32_t qa, uint32_t qb, uint32_t l) {
+    return n ? cuts_below(n, qa, qb, l) : 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -50,67 +59,89 @@ constexpr int kScanWaves = kScanThreads / 64;
 
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanParams p) {
     __shared__ uint64_t wave_tot[kNumScans][kScanWaves];
-    __shared__ uint64_t carry[kNumScans];
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63u;
     const uint32_t wave = tid >> 6;
-    if (tid < kNumScans) carry[tid] = 0;
-    __syncthreads();
+    const uint32_t num_waves = blockDim.x >> 6; // the launch sizes the workgroup to the batch, up to kScanThreads
+    uint64_t carry[kNumScans]; // sums over all earlier passes; every lane keeps the same copy
+#pragma unroll
+    for (int k = 0; k < kNumScans; ++k) carry[k] = 0;
 
-    for (uint32_t base = 0; base < p.num_requests; base += kScanThreads) {
+    for (uint32_t base = 0; base < p.num_requests; base += blockDim.x) {
         const uint32_t r = base + tid;
         uint64_t v[kNumScans];
 #pragma unroll
         for (int k = 0; k < kNumScans; ++k) v[k] = 0;
         if (r < p.num_requests) {
-            const uint64_t n = p.seq_lens[r];
+            const uint32_t n = p.seq_lens[r];
             v[SCAN_TOKENS] = n;
-            v[SCAN_PAGES_S] = p.page_s ? (n + p.page_s - 1) / p.page_s : 0;
-            v[SCAN_PAGES_D] = p.page_d ? (n + p.page_d - 1) / p.page_d : 0;
+            v[SCAN_PAGES_S] = p.page_s ? ceil_div_q(n, p.page_s) : 0;
+            v[SCAN_PAGES_D] = p.page_d ? ceil_div_q(n, p.page_d) : 0;
 #pragma unroll
             for (int op = 0; op < (int)NUM_OPS; ++op)
-                v[SCAN_RUNS0 + op] = p.planned[op] ? count_runs(n, p.qa[op], p.qb[op], p.lcm[op]) : 0;
+                v[SCAN_RUNS0 + op] = p.planned[op] ? count_runs(n, p.qa[op], p.qb[op], clamp_lcm(p.lcm[op])) : 0;
             if (p.planned[OP_CONVERT]) // slots, not runs: a fixed number per group
-                v[(int)SCAN_RUNS0 + (int)OP_CONVERT] = (n + p.group_quantum - 1) / p.group_quantum * p.group_slots;
+                v[(int)SCAN_RUNS0 + (int)OP_CONVERT] = (uint64_t)ceil_div_q(n, p.group_quantum) * p.group_slots;
         }
+        // The six scans advance together, step by step: the shuffles of one step are independent of each
+        // other, so their latencies overlap instead of adding up.
         uint64_t inc[kNumScans];
 #pragma unroll
+        for (int k = 0; k < kNumScans; ++k) inc[k] = v[k];
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            uint64_t y[kNumScans];
+#pragma unroll
+            for (int k = 0; k < kNumScans; ++k) y[k] = __shfl_up(inc[k], d, 64);
+#pragma unroll
+            for (int k = 0; k < kNumScans; ++k)
+                if ((int)lane >= d) inc[k] += y[k];
+        }
+        if (lane == 63) {
+#pragma unroll
+            for (int k = 0; k < kNumScans; ++k) wave_tot[k][wave] = inc[k];
+        }
+        __syncthreads();
+        // second level inside every wave: lanes 0..15 scan the (at most sixteen) wave totals with four more
+        // shuffle steps; no lane walks a chain of dependent LDS reads
+        uint64_t t[kNumScans], x[kNumScans];
+#pragma unroll
+        for (int k = 0; k < kNumScans; ++k) x[k] = t[k] = lane < num_waves ? wave_tot[k][lane] : 0;
+#pragma unroll
+        for (int d = 1; d < kScanWaves; d <<= 1) {
+            uint64_t y[kNumScans];
+#pragma unroll
+            for (int k = 0; k < kNumScans; ++k) y[k] = __shfl_up(x[k], d, 64);
+#pragma unroll
+            for (int k = 0; k < kNumScans; ++k)
+                if ((int)lane >= d) x[k] += y[k];
+        }
+#pragma unroll
         for (int k = 0; k < kNumScans; ++k) {
-            uint64_t x = v[k];
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                uint64_t y = __shfl_up(x, d, 64);
-                if ((int)lane >= d) x += y;
-            }
-            inc[k] = x;
-            if (lane == 63) wave_tot[k][wave] = x;
+            const uint64_t before = __shfl(x[k] - t[k], (int)wave, 64);
+            const uint64_t all = __shfl(x[k], kScanWaves - 1, 64);
+            if (r < p.num_requests) p.prefix[k][r] = carry[k] + before + inc[k] - v[k];
+            carry[k] += all;
         }
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < kNumScans; ++k) {
-            uint64_t before = carry[k];
-            for (uint32_t w = 0; w < wave; ++w) before += wave_tot[k][w];
-            if (r < p.num_requests) p.prefix[k][r] = before + inc[k] - v[k];
-            inc[k] += before; // inclusive, global
-        }
-        __syncthreads();
-        if (tid == kScanThreads - 1) {
-#pragma unroll
-            for (int k = 0; k < kNumScans; ++k) carry[k] = inc[k];
-        }
-        __syncthreads();
+        __syncthreads(); // the next pass overwrites the wave totals
     }
-    if (tid < kNumScans) p.prefix[tid][p.num_requests] = carry[tid];
+    if (tid < kNumScans) {
+        // carry is indexed by a run-time value here: pick it without spilling the array
+        uint64_t total = 0;
+#pragma unroll
+        for (int k = 0; k < kNumScans; ++k) total = (int)tid == k ? carry[k] : total;
+        p.prefix[tid][p.num_requests] = total;
+    }
 }
 
 // ---------------------------------------------------------------------------
 // fill
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ uint64_t side_offset(const SideGeom &g, uint32_t r, uint64_t x,
+__device__ __forceinline__ uint64_t side_offset(const SideGeom &g, uint32_t r, uint32_t x,
                                                 uint64_t buf_base, uint32_t row) {
-    if (g.quantum == 0) return buf_base + x * row;
-    const uint64_t logical = x / g.page_tokens;
-    const uint64_t slot = x % g.page_tokens;
+    if (g.quantum == 0) return buf_base + (uint64_t)x * row;
+    const uint32_t logical = x / g.page_tokens;
+    const uint32_t slot = x - logical * g.page_tokens;
     const uint64_t page = g.ids[g.page_prefix[r] + logical];
     return page * g.stride_page + slot * g.stride_token;
 }
@@ -123,9 +154,9 @@ __global__ __launch_bounds__(kFillThreads) void fill_kernel(FillParams p) {
     if (!p.planned[op]) return;
     const SideGeom &a = p.src[op];
     const SideGeom &b = p.dst[op];
-    const uint64_t l = p.lcm[op];
+    const uint32_t l = clamp_lcm(p.lcm[op]);
     for (uint32_t r = blockIdx.x; r < p.num_requests; r += gridDim.x) {
-        const uint64_t n = p.seq_lens[r];
+        const uint32_t n = p.seq_lens[r];
         if (n == 0) continue;
         const uint64_t ca = ceil_div_q(n, a.quantum);
         const uint64_t cb = ceil_div_q(n, b.quantum);
@@ -139,33 +170,33 @@ __global__ __launch_bounds__(kFillThreads) void fill_kernel(FillParams p) {
             for (uint64_t i = threadIdx.x; i < slots; i += kFillThreads) out[i] = none;
             __syncthreads();
         }
+        // one thread per cut point: the ca multiples of a's quantum, then the cb multiples of b's (all below n)
         for (uint64_t i = threadIdx.x; i < ca + cb; i += kFillThreads) {
-            uint64_t x;
+            uint32_t x;
             if (i < ca) {
-                x = i * a.quantum; // quantum 0 -> ca == 1 -> x == 0
+                x = (uint32_t)i * a.quantum; // quantum 0 -> ca == 1 -> x == 0
             } else {
-                x = (i - ca) * b.quantum;
+                x = (uint32_t)(i - ca) * b.quantum;
                 const bool also_a = a.quantum ? (x % a.quantum == 0) : (x == 0);
                 if (also_a) continue; // that boundary belongs to the other side's thread
             }
-            uint64_t rank = ceil_div_q(x, a.quantum) + ceil_div_q(x, b.quantum) - ceil_div_q(x, l);
+            uint64_t rank = cuts_below(x, a.quantum, b.quantum, l);
             if (grouped) {
                 // position = group * slots + rank among the boundaries inside the group
-                const uint64_t g = x / p.group_quantum;
-                const uint64_t g0 = g * p.group_quantum;
-                rank = g * p.group_slots + rank -
-                       (ceil_div_q(g0, a.quantum) + ceil_div_q(g0, b.quantum) - ceil_div_q(g0, l));
+                const uint32_t g = x / p.group_quantum;
+                const uint32_t g0 = g * p.group_quantum;
+                rank = (uint64_t)g * p.group_slots + rank - cuts_below(g0, a.quantum, b.quantum, l);
             }
             uint64_t end = n;
-            if (a.quantum) end = min(end, (x / a.quantum + 1) * a.quantum);
-            if (b.quantum) end = min(end, (x / b.quantum + 1) * b.quantum);
+            if (a.quantum) end = min(end, (uint64_t)(x / a.quantum + 1u) * a.quantum);
+            if (b.quantum) end = min(end, (uint64_t)(x / b.quantum + 1u) * b.quantum);
             kvx_run run;
             run.src_off = side_offset(a, r, x, buf_base, p.row);
             run.dst_off = side_offset(b, r, x, buf_base, p.row);
             run.bytes = (uint32_t)((end - x) * p.row);
-            run.seq_len = (uint32_t)n;
+            run.seq_len = n;
             run.request = r;
-            run.token = (uint32_t)x;
+            run.token = x;
             out[rank] = run;
         }
     }
@@ -426,7 +457,9 @@ __global__ __launch_bounds__(256) void chunk_copy_kernel(const uint32_t *__restr
         hipLaunchKernelGGL(__VA_ARGS__); \
     } while (0)
 hipError_t launch_scan(const ScanParams &p, hipStream_t stream) {
-    KVX_LAUNCH(scan_kernel, dim3(1), dim3(kScanThreads), 0, stream, p);
+    // whole waves, no more of them than the batch has requests for (a short batch then costs one wave's work)
+    const uint32_t threads = std::min<uint32_t>(kScanThreads, std::max<uint32_t>(64u, (p.num_requests + 63u) / 64u * 64u));
+    KVX_LAUNCH(scan_kernel, dim3(1), dim3(threads), 0, stream, p);
     return hipGetLastError();
 }
 

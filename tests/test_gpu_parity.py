@@ -270,6 +270,24 @@ def test_one_very_long_request():
     G.assert_same(got, want, "long request")
 
 
+def test_page_sizes_whose_lcm_exceeds_32_bits():
+    """Pages of 65 537 and 65 539 tokens (coprime: the two grids never meet again below 2^32 tokens), 16-byte
+    rows; the planner's run counts and ranks must not depend on the common multiple fitting a word."""
+    rng = np.random.default_rng(107)
+    case = G.make_case(rng, 1, 1, 8, 2, [150000, 70000, 65537, 65539, 5, 0], 65537, 65539, LM, LM, slack_pages=1)
+    src = rng.integers(0, 256, size=case.pool_bytes(case.s), dtype=np.uint8)
+    want = G.run_oracle(case, src, 0, 1)
+    got = G.run_gpu(case, src, 0, 1, want_tables=True)
+    G.assert_same(got, want, "huge lcm")
+    # runs of convert: one per cut of either grid -> ceil(n/Ps) + ceil(n/Pd) - 1 per non-empty request,
+    # stored in groups of (65539 // 65537 + 2) slots per receiver page
+    runs = got.extra["runs2"]
+    live = runs[runs["bytes"] > 0]
+    expect = sum(-(-n // 65537) + -(-n // 65539) - 1 for n in (150000, 70000, 65537, 65539, 5))
+    assert len(live) == expect
+    assert int(live["bytes"].astype(np.int64).sum()) == (150000 + 70000 + 65537 + 65539 + 5) * 16
+
+
 def test_wide_rows_and_large_pages():
     """64 KiB rows (64 heads x 256 x 4 bytes) in pages of 512 tokens: a 32 MiB page chunk."""
     rng = np.random.default_rng(104)
