@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per copy_kernel launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by the plain-copy calibration), valid only for the kernel source they were taken on.
 COUNTER_RUNS = {
-    "kernels_sha256": "c3336d3809b9f6940ae6bf87fb325d74c44292911ea40385bfec6560b26d3e2f",
-    "traffic_bytes_per_launch": {2: 12103896279, 3: 13228532258, 5: 47003697005, 4: 152991975213},
+    "kernels_sha256": "88aef6cdd17bcf9fdf7bb71d272ae9116e90dd3539da1269fb842dc2ee948940",
+    "traffic_bytes_per_launch": {2: 12103902243, 3: 13228532337, 5: 47003811406, 4: 152992018345},
 }
 
 

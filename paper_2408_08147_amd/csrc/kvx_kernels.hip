@@ -57,6 +57,37 @@ __device__ __forceinline__ uint64_t count_runs(uint32_t n, uint32_t qa, uint32_t
 constexpr int kScanThreads = 1024;
 constexpr int kScanWaves = kScanThreads / 64;
 
+// x + (x of another lane), the other lane picked by a data-parallel-primitive control word: the value moves
+// inside the vector ALU, not through the LDS crossbar that shuffles use (sixteen waves of shuffles on one
+// compute unit were most of this kernel's time).  Lanes the control leaves without a source add 0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint64_t dpp_add(uint64_t x) {
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)x, CTRL, ROW_MASK, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(x >> 32), CTRL, ROW_MASK, 0xF, true);
+    return x + (((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+// Inclusive sum over each row of 16 lanes: shifts by 1, 2, 4 and 8 lanes that stop at the row's first lane.
+__device__ __forceinline__ uint64_t row_inclusive_sum(uint64_t x) {
+    x = dpp_add<0x111, 0xF>(x); // row_shr:1
+    x = dpp_add<0x112, 0xF>(x); // row_shr:2
+    x = dpp_add<0x114, 0xF>(x); // row_shr:4
+    x = dpp_add<0x118, 0xF>(x); // row_shr:8
+    return x;
+}
+// Inclusive sum over the 64 lanes: rows first, then lane 15 of rows 0 and 2 into rows 1 and 3
+// (row_bcast:15), then lane 31 into rows 2 and 3 (row_bcast:31).
+__device__ __forceinline__ uint64_t wave_inclusive_sum(uint64_t x) {
+    x = row_inclusive_sum(x);
+    x = dpp_add<0x142, 0xA>(x);
+    x = dpp_add<0x143, 0xC>(x);
+    return x;
+}
+__device__ __forceinline__ uint64_t read_lane(uint64_t x, int lane) { // lane is the same for the whole wave
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, lane);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), lane);
+    return ((uint64_t)hi << 32) | lo;
+}
+
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanParams p) {
     __shared__ uint64_t wave_tot[kNumScans][kScanWaves];
     const uint32_t tid = threadIdx.x;
@@ -83,43 +114,22 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanParams p) {
             if (p.planned[OP_CONVERT]) // slots, not runs: a fixed number per group
                 v[(int)SCAN_RUNS0 + (int)OP_CONVERT] = (uint64_t)ceil_div_q(n, p.group_quantum) * p.group_slots;
         }
-        // The six scans advance together, step by step: the shuffles of one step are independent of each
-        // other, so their latencies overlap instead of adding up.
         uint64_t inc[kNumScans];
 #pragma unroll
-        for (int k = 0; k < kNumScans; ++k) inc[k] = v[k];
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            uint64_t y[kNumScans];
-#pragma unroll
-            for (int k = 0; k < kNumScans; ++k) y[k] = __shfl_up(inc[k], d, 64);
-#pragma unroll
-            for (int k = 0; k < kNumScans; ++k)
-                if ((int)lane >= d) inc[k] += y[k];
-        }
+        for (int k = 0; k < kNumScans; ++k) inc[k] = wave_inclusive_sum(v[k]);
         if (lane == 63) {
 #pragma unroll
             for (int k = 0; k < kNumScans; ++k) wave_tot[k][wave] = inc[k];
         }
         __syncthreads();
-        // second level inside every wave: lanes 0..15 scan the (at most sixteen) wave totals with four more
-        // shuffle steps; no lane walks a chain of dependent LDS reads
-        uint64_t t[kNumScans], x[kNumScans];
-#pragma unroll
-        for (int k = 0; k < kNumScans; ++k) x[k] = t[k] = lane < num_waves ? wave_tot[k][lane] : 0;
-#pragma unroll
-        for (int d = 1; d < kScanWaves; d <<= 1) {
-            uint64_t y[kNumScans];
-#pragma unroll
-            for (int k = 0; k < kNumScans; ++k) y[k] = __shfl_up(x[k], d, 64);
-#pragma unroll
-            for (int k = 0; k < kNumScans; ++k)
-                if ((int)lane >= d) x[k] += y[k];
-        }
+        // second level inside every wave: its lanes 0..15 (one row) scan the at most sixteen wave totals
+        const int my_wave = __builtin_amdgcn_readfirstlane((int)wave);
 #pragma unroll
         for (int k = 0; k < kNumScans; ++k) {
-            const uint64_t before = __shfl(x[k] - t[k], (int)wave, 64);
-            const uint64_t all = __shfl(x[k], kScanWaves - 1, 64);
+            const uint64_t t = lane < num_waves ? wave_tot[k][lane] : 0;
+            const uint64_t x = row_inclusive_sum(t);
+            const uint64_t before = read_lane(x - t, my_wave);
+            const uint64_t all = read_lane(x, kScanWaves - 1);
             if (r < p.num_requests) p.prefix[k][r] = carry[k] + before + inc[k] - v[k];
             carry[k] += all;
         }
