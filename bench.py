@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per copy_kernel launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by the plain-copy calibration), valid only for the kernel source they were taken on.
 COUNTER_RUNS = {
-    "kernels_sha256": "88aef6cdd17bcf9fdf7bb71d272ae9116e90dd3539da1269fb842dc2ee948940",
-    "traffic_bytes_per_launch": {2: 12103902243, 3: 13228532337, 5: 47003811406, 4: 152992018345},
+    "kernels_sha256": "f54f02d5d1114622cee99ffca6d1e82e836d377aa40779e9d24e91c607b1b45a",
+    "traffic_bytes_per_launch": {2: 12103910276, 3: 13228530923, 5: 47003657206, 4: 152995878056},
 }
 
 

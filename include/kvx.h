@@ -22,8 +22,8 @@
  *     and nothing else, so these calls (and their _layers forms) may be recorded
  *     while `stream` is being captured into a HIP graph; the graph then needs
  *     the plan's workspace and the pools at the same addresses on every replay.
- *     kvx_plan itself copies from a staging block that the library reuses and
- *     records an event, and must not be called on a capturing stream.
+ *     kvx_plan itself may copy from a staging block that the library reuses
+ *     and record an event, and must not be called on a capturing stream.
  *   - Every call returns a kvx_status; nothing aborts or throws.  All argument,
  *     geometry and block-table checks happen on the host inside kvx_plan, and a
  *     plan that fails leaves the workspace untouched.
@@ -178,11 +178,12 @@ kvx_status kvx_plan_workspace_bytes(const kvx_pool_desc *s, const kvx_batch_desc
  * size and precision, and the "meta" exchanged before a transfer.
  *
  * Host part: validates everything (see kvx_status), computes T_r and the
- * payload size.  Device part, enqueued on `stream`: one copy of lengths and
- * block tables into the workspace, a wavefront prefix-scan kernel over the
- * variable lengths, and a kernel that writes the kvx_run records.  The plan
- * may be used on `stream` right away, and on other streams after `stream` has
- * been synchronised with them.
+ * payload size.  Device part, enqueued on `stream`: lengths and used page ids
+ * go into the workspace (inside the next kernel's launch arguments when they
+ * are at most 896 words together, else staged in pinned memory and copied),
+ * a wavefront prefix-scan kernel over the variable lengths, and a kernel that
+ * writes the kvx_run records.  The plan may be used on `stream` right away,
+ * and on other streams after `stream` has been synchronised with them.
  *
  * With a sender side the plan serves kvx_pack, with a receiver side
  * kvx_unpack, with both also kvx_convert.  Both sides must then agree in

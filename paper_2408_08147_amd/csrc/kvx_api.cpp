@@ -446,16 +446,34 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
         if (workspace_bytes < z.total_bytes) return KVX_ERR_CAPACITY;
         p->ws = static_cast<char *>(dev_workspace);
         hipStream_t hs = static_cast<hipStream_t>(stream);
-        if (!hip_ok(pinned_acquire((size_t)std::max<uint64_t>(z.staging_bytes, 16), &p->staging),
-                    "pinned staging block")) return KVX_ERR_DEVICE;
-        char *h = static_cast<char *>(p->staging.ptr);
-        if (R) std::memcpy(h + z.off_lens, p->seq_lens.data(), 4ull * R);
-        if (!ids_s.empty()) std::memcpy(h + z.off_ids_s, ids_s.data(), 4ull * ids_s.size());
-        if (!ids_d.empty()) std::memcpy(h + z.off_ids_d, ids_d.data(), 4ull * ids_d.size());
+        // Tables of a small batch ride in the scan kernel's arguments; larger ones are staged in pinned
+        // memory and copied.
+        const uint64_t table_words = (uint64_t)R + ids_s.size() + ids_d.size();
+        const bool tables_inline = table_words <= kInlineWords;
         bool ok = true;
-        if (z.staging_bytes)
+        InlineTables it;
+        if (tables_inline) {
+            const uint32_t *seg[3] = {p->seq_lens.data(), ids_s.data(), ids_d.data()};
+            const uint64_t off[3] = {z.off_lens, z.off_ids_s, z.off_ids_d};
+            uint32_t at = 0;
+            it.count[0] = R;
+            it.count[1] = (uint32_t)ids_s.size();
+            it.count[2] = (uint32_t)ids_d.size();
+            for (int k = 0; k < 3; ++k) {
+                it.dst_word[k] = (uint32_t)(off[k] / 4);
+                if (it.count[k]) std::memcpy(it.words + at, seg[k], 4ull * it.count[k]);
+                at += it.count[k];
+            }
+        } else {
+            if (!hip_ok(pinned_acquire((size_t)z.staging_bytes, &p->staging), "pinned staging block"))
+                return KVX_ERR_DEVICE;
+            char *h = static_cast<char *>(p->staging.ptr);
+            if (R) std::memcpy(h + z.off_lens, p->seq_lens.data(), 4ull * R);
+            if (!ids_s.empty()) std::memcpy(h + z.off_ids_s, ids_s.data(), 4ull * ids_s.size());
+            if (!ids_d.empty()) std::memcpy(h + z.off_ids_d, ids_d.data(), 4ull * ids_d.size());
             ok = hip_ok(hipMemcpyAsync(p->ws, h, z.staging_bytes, hipMemcpyHostToDevice, hs), "copy of the tables");
-        ok = ok && hip_ok(hipEventRecord(p->staging.copied, hs), "event behind the copy");
+            ok = ok && hip_ok(hipEventRecord(p->staging.copied, hs), "event behind the copy");
+        }
 
         ScanParams sp{};
         sp.seq_lens = reinterpret_cast<const uint32_t *>(p->ws + z.off_lens);
@@ -503,7 +521,11 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
             fp.run_prefix[op] = sp.prefix[SCAN_RUNS0 + op];
             fp.runs[op] = reinterpret_cast<kvx_run *>(p->ws + z.off_runs[op]);
         }
-        ok = ok && hip_ok(launch_scan(sp, hs), "scan_kernel launch");
+        if (tables_inline)
+            ok = ok && hip_ok(launch_scan_inline(sp, it, reinterpret_cast<uint32_t *>(p->ws), hs),
+                              "scan_inline_kernel launch");
+        else
+            ok = ok && hip_ok(launch_scan(sp, hs), "scan_kernel launch");
         ok = ok && hip_ok(launch_fill(fp, hs), "fill_kernel launch");
         if (!ok) {
             pinned_release(p->staging);

@@ -47,6 +47,17 @@ struct ScanParams {
     uint64_t *prefix[kNumScans]; // outputs
 };
 
+// Small batches hand their tables (lengths, then the sender's used page ids, then the receiver's) to the scan
+// kernel inside its arguments: the launch itself carries them to the device, so there is no host-to-device
+// copy to issue, no staging block to keep alive and no event to record.  The kernel stores the three
+// segments at dst_word[] (32-bit words from the start of the workspace) for the kernels that follow.
+constexpr uint32_t kInlineWords = 896; // with ScanParams this stays under the 4 KiB a launch may carry
+struct InlineTables {
+    uint32_t count[3];
+    uint32_t dst_word[3];
+    uint32_t words[kInlineWords];
+};
+
 struct FillParams {
     const uint32_t *seq_lens;
     const uint64_t *token_prefix;
@@ -122,6 +133,8 @@ inline bool valid_threads(uint32_t t) { return t == 64 || t == 128 || t == 256 |
 inline bool valid_unroll(uint32_t u) { return u == 1 || u == 2 || u == 4 || u == 8; }
 
 hipError_t launch_scan(const ScanParams &p, hipStream_t stream);
+hipError_t launch_scan_inline(const ScanParams &p, const InlineTables &t, uint32_t *workspace_words,
+                              hipStream_t stream);
 hipError_t launch_fill(const FillParams &p, hipStream_t stream);
 hipError_t launch_copy(const CopyParams &p, uint32_t threads, uint32_t unroll, int nontemporal, uint32_t grid,
                        uint32_t lds_bytes, hipStream_t stream);

@@ -88,7 +88,9 @@ __device__ __forceinline__ uint64_t read_lane(uint64_t x, int lane) { // lane is
     return ((uint64_t)hi << 32) | lo;
 }
 
-__global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanParams p) {
+// `length_of(r)` reads request r's length: from the workspace, or straight from the launch arguments.
+template <typename Lengths>
+__device__ __forceinline__ void scan_body(const ScanParams &p, Lengths length_of) {
     __shared__ uint64_t wave_tot[kNumScans][kScanWaves];
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63u;
@@ -104,7 +106,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanParams p) {
 #pragma unroll
         for (int k = 0; k < kNumScans; ++k) v[k] = 0;
         if (r < p.num_requests) {
-            const uint32_t n = p.seq_lens[r];
+            const uint32_t n = length_of(r);
             v[SCAN_TOKENS] = n;
             v[SCAN_PAGES_S] = p.page_s ? ceil_div_q(n, p.page_s) : 0;
             v[SCAN_PAGES_D] = p.page_d ? ceil_div_q(n, p.page_d) : 0;
@@ -142,6 +144,35 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanParams p) {
         for (int k = 0; k < kNumScans; ++k) total = (int)tid == k ? carry[k] : total;
         p.prefix[tid][p.num_requests] = total;
     }
+}
+
+__global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanParams p) {
+    scan_body(p, [&](uint32_t r) { return p.seq_lens[r]; });
+}
+
+// The same scan for a batch whose tables arrive in the launch arguments; it first puts them where the
+// kernels after it expect them.  (The lengths are read from the arguments, not back from memory.)
+__global__ __launch_bounds__(kScanThreads) void scan_inline_kernel(ScanParams p, InlineTables t,
+                                                                   uint32_t *__restrict__ workspace_words) {
+    const uint32_t c0 = t.count[0], c01 = c0 + t.count[1], total = c01 + t.count[2];
+    constexpr int kPerLane = 4; // reads of the arguments in flight per lane before the first store
+    for (uint32_t base = 0; base < total; base += blockDim.x * kPerLane) {
+        uint32_t w[kPerLane];
+#pragma unroll
+        for (int k = 0; k < kPerLane; ++k) {
+            const uint32_t i = base + k * blockDim.x + threadIdx.x;
+            if (i < total) w[k] = t.words[i];
+        }
+#pragma unroll
+        for (int k = 0; k < kPerLane; ++k) {
+            const uint32_t i = base + k * blockDim.x + threadIdx.x;
+            if (i >= total) continue;
+            const uint32_t seg = i < c0 ? 0u : (i < c01 ? 1u : 2u);
+            const uint32_t j = i - (seg == 0u ? 0u : (seg == 1u ? c0 : c01));
+            workspace_words[t.dst_word[seg] + j] = w[k];
+        }
+    }
+    scan_body(p, [&](uint32_t r) { return t.words[r]; });
 }
 
 // ---------------------------------------------------------------------------
@@ -470,6 +501,17 @@ hipError_t launch_scan(const ScanParams &p, hipStream_t stream) {
     // whole waves, no more of them than the batch has requests for (a short batch then costs one wave's work)
     const uint32_t threads = std::min<uint32_t>(kScanThreads, std::max<uint32_t>(64u, (p.num_requests + 63u) / 64u * 64u));
     KVX_LAUNCH(scan_kernel, dim3(1), dim3(threads), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_scan_inline(const ScanParams &p, const InlineTables &t, uint32_t *workspace_words,
+                              hipStream_t stream) {
+    // waves for the requests, and up to four of them so that one round of reads moves all the words
+    const uint32_t words = t.count[0] + t.count[1] + t.count[2];
+    const uint32_t for_requests = std::max<uint32_t>(64u, (p.num_requests + 63u) / 64u * 64u);
+    const uint32_t for_words = std::min<uint32_t>(256u, (words / 4u + 63u) / 64u * 64u);
+    const uint32_t threads = std::min<uint32_t>(kScanThreads, std::max(for_requests, for_words));
+    KVX_LAUNCH(scan_inline_kernel, dim3(1), dim3(threads), 0, stream, p, t, workspace_words);
     return hipGetLastError();
 }
 

@@ -188,6 +188,49 @@ def test_device_plan_tables(Ps, Pd):
             assert np.array_equal(runs["dst_off"].astype(np.int64), buf_off)
 
 
+@pytest.mark.parametrize("pages_second", [45, 46, 47, 48, 49])
+def test_tables_on_either_side_of_the_launch_argument_limit(pages_second):
+    """Small batches hand their tables to the device inside a kernel's launch arguments (896 words: lengths
+    plus both sides' used page ids), larger ones through a staged copy.  2 requests with 400 + k pages per
+    side give 2 + 2*(400 + k) words: k = 47 is the last that fits."""
+    rng = np.random.default_rng(500 + pages_second)
+    lens = [16 * 400 - 3, 16 * pages_second - 5]
+    case = G.make_case(rng, 2, 1, 16, 1, lens, 16, 16, LM, PM)
+    words = 2 + 2 * (400 + pages_second)
+    assert (words <= 896) == (pages_second <= 47)
+    check(case, 600 + pages_second)
+
+
+def test_sender_only_and_receiver_only_plans_inline_and_staged():
+    """One-sided plans (what a real sender or receiver builds) through both table paths."""
+    import torch
+    dev = torch.device("cuda:0")
+    for n_pages in (20, 1000):   # 1 + 20 words ride in the launch arguments, 1 + 1000 are staged and copied
+        rng = np.random.default_rng(n_pages)
+        case = G.make_case(rng, 2, 2, 16, 2, [16 * n_pages - 7], 16, 16, LM, LM)
+        src = rng.integers(0, 256, size=case.pool_bytes(case.s), dtype=np.uint8)
+        want = G.run_oracle(case, src, 0, 2)
+        sb = kvx.BatchDesc(case.seq_lens, case.ids_s, case.offs_s)
+        db = kvx.BatchDesc(case.seq_lens, case.ids_d, case.offs_d)
+        sp, dp = case.kvx_pool(case.s), case.kvx_pool(case.d)
+        stream = torch.cuda.Stream(device=dev)
+        with torch.cuda.stream(stream):
+            src_t = torch.from_numpy(src).to(dev)
+            ws_s = torch.zeros(kvx.kvx_plan_workspace_bytes(sp, sb, None, None), dtype=torch.uint8, device=dev)
+            ws_d = torch.zeros(kvx.kvx_plan_workspace_bytes(None, None, dp, db), dtype=torch.uint8, device=dev)
+            buf = torch.full((want.total + G.BUF_SLACK,), G.CANARY_BUF, dtype=torch.uint8, device=dev)
+            dst = torch.full((case.pool_bytes(case.d),), G.CANARY_POOL, dtype=torch.uint8, device=dev)
+            ps = kvx.kvx_plan(sp, sb, None, None, 0, 2, ws_s.data_ptr(), ws_s.numel(), stream.cuda_stream)
+            pd = kvx.kvx_plan(None, None, dp, db, 0, 2, ws_d.data_ptr(), ws_d.numel(), stream.cuda_stream)
+            kvx.kvx_pack(ps, src_t.data_ptr(), buf.data_ptr(), want.total, stream.cuda_stream)
+            kvx.kvx_unpack(pd, buf.data_ptr(), want.total, dst.data_ptr(), stream.cuda_stream)
+            ps.destroy()
+            pd.destroy()
+        stream.synchronize()
+        assert np.array_equal(buf.cpu().numpy(), want.buf), n_pages
+        assert np.array_equal(dst.cpu().numpy(), want.dst_unpack), n_pages
+
+
 def test_plan_reuse_and_immediate_destroy():
     """A plan can be used many times, and destroyed right after enqueueing."""
     import torch
