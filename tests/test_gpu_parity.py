@@ -201,34 +201,57 @@ def test_tables_on_either_side_of_the_launch_argument_limit(pages_second):
     check(case, 600 + pages_second)
 
 
-def test_sender_only_and_receiver_only_plans_inline_and_staged():
-    """One-sided plans (what a real sender or receiver builds) through both table paths."""
+ONE_SIDED = {
+    # tables in the scan kernel's launch arguments
+    "one_request": [16 * 20 - 7],
+    "four_requests": [100, 0, 33, 16],
+    "sixty_five_requests": [9] * 65,
+    "one_request_895_pages": [16 * 895 - 1],        # 1 + 895 words: the most the launch arguments take
+    # tables staged in pinned memory and copied
+    "one_request_896_pages": [16 * 896],
+    "one_request_2000_pages": [16 * 2000 - 7],
+}
+
+
+@pytest.mark.parametrize("name", sorted(ONE_SIDED))
+def test_sender_only_and_receiver_only_plans(name):
+    """One-sided plans (what a real sender or receiver builds) through both ways the tables reach the device."""
     import torch
     dev = torch.device("cuda:0")
-    for n_pages in (20, 1000):   # 1 + 20 words ride in the launch arguments, 1 + 1000 are staged and copied
-        rng = np.random.default_rng(n_pages)
-        case = G.make_case(rng, 2, 2, 16, 2, [16 * n_pages - 7], 16, 16, LM, LM)
-        src = rng.integers(0, 256, size=case.pool_bytes(case.s), dtype=np.uint8)
-        want = G.run_oracle(case, src, 0, 2)
-        sb = kvx.BatchDesc(case.seq_lens, case.ids_s, case.offs_s)
-        db = kvx.BatchDesc(case.seq_lens, case.ids_d, case.offs_d)
-        sp, dp = case.kvx_pool(case.s), case.kvx_pool(case.d)
-        stream = torch.cuda.Stream(device=dev)
-        with torch.cuda.stream(stream):
-            src_t = torch.from_numpy(src).to(dev)
-            ws_s = torch.zeros(kvx.kvx_plan_workspace_bytes(sp, sb, None, None), dtype=torch.uint8, device=dev)
-            ws_d = torch.zeros(kvx.kvx_plan_workspace_bytes(None, None, dp, db), dtype=torch.uint8, device=dev)
-            buf = torch.full((want.total + G.BUF_SLACK,), G.CANARY_BUF, dtype=torch.uint8, device=dev)
-            dst = torch.full((case.pool_bytes(case.d),), G.CANARY_POOL, dtype=torch.uint8, device=dev)
-            ps = kvx.kvx_plan(sp, sb, None, None, 0, 2, ws_s.data_ptr(), ws_s.numel(), stream.cuda_stream)
-            pd = kvx.kvx_plan(None, None, dp, db, 0, 2, ws_d.data_ptr(), ws_d.numel(), stream.cuda_stream)
-            kvx.kvx_pack(ps, src_t.data_ptr(), buf.data_ptr(), want.total, stream.cuda_stream)
-            kvx.kvx_unpack(pd, buf.data_ptr(), want.total, dst.data_ptr(), stream.cuda_stream)
-            ps.destroy()
-            pd.destroy()
-        stream.synchronize()
-        assert np.array_equal(buf.cpu().numpy(), want.buf), n_pages
-        assert np.array_equal(dst.cpu().numpy(), want.dst_unpack), n_pages
+    lens = ONE_SIDED[name]
+    rng = np.random.default_rng(len(lens) + sum(lens))
+    case = G.make_case(rng, 2, 2, 16, 2, lens, 16, 16, LM, LM)
+    src = rng.integers(0, 256, size=case.pool_bytes(case.s), dtype=np.uint8)
+    want = G.run_oracle(case, src, 0, 2)
+    sb = kvx.BatchDesc(case.seq_lens, case.ids_s, case.offs_s)
+    db = kvx.BatchDesc(case.seq_lens, case.ids_d, case.offs_d)
+    sp, dp = case.kvx_pool(case.s), case.kvx_pool(case.d)
+    stream = torch.cuda.Stream(device=dev)
+    with torch.cuda.stream(stream):
+        src_t = torch.from_numpy(src).to(dev)
+        ws_s = torch.zeros(kvx.kvx_plan_workspace_bytes(sp, sb, None, None), dtype=torch.uint8, device=dev)
+        ws_d = torch.zeros(kvx.kvx_plan_workspace_bytes(None, None, dp, db), dtype=torch.uint8, device=dev)
+        buf = torch.full((want.total + G.BUF_SLACK,), G.CANARY_BUF, dtype=torch.uint8, device=dev)
+        dst = torch.full((case.pool_bytes(case.d),), G.CANARY_POOL, dtype=torch.uint8, device=dev)
+        ps = kvx.kvx_plan(sp, sb, None, None, 0, 2, ws_s.data_ptr(), ws_s.numel(), stream.cuda_stream)
+        pd = kvx.kvx_plan(None, None, dp, db, 0, 2, ws_d.data_ptr(), ws_d.numel(), stream.cuda_stream)
+        kvx.kvx_pack(ps, src_t.data_ptr(), buf.data_ptr(), want.total, stream.cuda_stream)
+        kvx.kvx_unpack(pd, buf.data_ptr(), want.total, dst.data_ptr(), stream.cuda_stream)
+        ps.destroy()
+        pd.destroy()
+    stream.synchronize()
+    assert np.array_equal(buf.cpu().numpy(), want.buf)
+    assert np.array_equal(dst.cpu().numpy(), want.dst_unpack)
+
+
+@pytest.mark.parametrize("lens,Ps,Pd", [([77], 16, 16), ([1], 16, 4), ([4000], 128, 16), ([1700], 5, 7),
+                                        ([16 * 447], 16, 16), ([16 * 447 + 1], 16, 16)])
+def test_single_request_two_sided_plans(lens, Ps, Pd):
+    """One request with both sides given, around the point where its tables stop fitting the launch
+    arguments (1 + 2 x 447 words do, 1 + 2 x 448 do not)."""
+    rng = np.random.default_rng(lens[0] + Ps)
+    case = G.make_case(rng, 2, 1, 16, 1, lens, Ps, Pd, LM, PM)
+    check(case, lens[0] + Pd)
 
 
 def test_plan_reuse_and_immediate_destroy():
