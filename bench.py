@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per copy_kernel launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by the plain-copy calibration), valid only for the kernel source they were taken on.
 COUNTER_RUNS = {
-    "kernels_sha256": "f54f02d5d1114622cee99ffca6d1e82e836d377aa40779e9d24e91c607b1b45a",
-    "traffic_bytes_per_launch": {2: 12103910276, 3: 13228530923, 5: 47003657206, 4: 152995878056},
+    "kernels_sha256": "8c263f79743b9fb08232d9f521b9341e5f44fd8f24ea11d7197ebb9cf610b354",
+    "traffic_bytes_per_launch": {2: 12103875604, 3: 13228397731, 5: 47001472844, 4: 152992097585},
 }
 
 

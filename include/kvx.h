@@ -127,8 +127,10 @@ typedef struct {
     uint32_t nontemporal;   /* cache policy of the 16-byte accesses: 0 = chosen per operation, 1 = default,
                                2 = non-temporal loads and stores, 3 = non-temporal loads with agent-scope
                                (write-through) stores */
-    uint32_t order;         /* 0 = chosen per operation from the receiver's layout, 1 = (layer,kv) outermost,
-                               2 = copy run (for convert: group of runs) outermost */
+    uint32_t order;         /* 0 = chosen per operation (pack: 3; unpack and convert: 2 into a page-major
+                               receiver, else 1), 1 = (layer,kv) outermost, 2 = copy run (for convert: group of
+                               runs) outermost, 3 = the runs cut into eight parts, one per XCD, each part walked
+                               with (layer,kv) outermost ([token][head][dim] pages only, else as 1) */
     uint32_t xcd_swizzle;   /* 1 = off, 2 = give each of the 8 XCDs contiguous tiles: one eighth of the grid
                                each, or blocks of `xcd_block_tiles` tiles dealt round-robin */
     uint32_t max_workgroups;/* cap on the grid; tiles beyond it are taken in a grid-stride loop */

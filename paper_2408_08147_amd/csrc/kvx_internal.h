@@ -87,7 +87,8 @@ struct CopyParams {
     uint32_t num_runs;
     uint32_t tiles_per_run;
     uint32_t total_tiles;     // num_lc * num_runs * tiles_per_run
-    uint32_t order;           // 1: (layer,kv) outermost   2: run group outermost
+    uint32_t order;           // 1: (layer,kv) outermost   2: run group outermost   3: eighth of the runs outermost
+    uint32_t runs_per_part;   // order 3: ceil(num_runs / 8); total_tiles then counts 8 * runs_per_part runs
     uint32_t group;           // order 2: consecutive runs that stay together inside one (layer,kv)
     uint32_t swizzle_chunk;   // 0 = off, else tiles per XCD (grid is a multiple of 8)
     uint32_t swizzle_block;   // 0 = eighths of the grid, else tiles per block dealt round-robin to the XCDs

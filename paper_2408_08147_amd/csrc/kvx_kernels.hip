@@ -291,12 +291,25 @@ __global__ __launch_bounds__(T) void copy_kernel(const kvx_run *__restrict__ run
         first = (blockIdx.x & 7u) * p.swizzle_chunk + (blockIdx.x >> 3);
     }
 
+    // Order 3 deals the tiles out one by one: tile v belongs to part v mod 8 of the runs, and with a grid that is
+    // a multiple of 8 a workgroup stays with its part, the one its XCD works on.
+    if (p.order == 3) first = blockIdx.x;
+
     for (uint64_t v64 = first; v64 < p.total_tiles; v64 += gridDim.x) {
-        const uint32_t v = (uint32_t)v64;
+        uint32_t v = (uint32_t)v64;
         uint32_t lc, e;
+        uint32_t part = 0;
+        if (p.order == 3) {
+            part = v & 7u;
+            v >>= 3;
+        }
         const uint32_t s = v % p.tiles_per_run;
         const uint32_t q = v / p.tiles_per_run;
-        if (p.order == 2) {
+        if (p.order == 3) {
+            e = part * p.runs_per_part + q % p.runs_per_part;
+            lc = q / p.runs_per_part;
+            if (e >= p.num_runs) continue; // the last part may be short
+        } else if (p.order == 2) {
             const uint32_t i = q % p.group;
             const uint32_t q2 = q / p.group;
             lc = q2 % p.num_lc;

@@ -42,7 +42,7 @@ def test_inner_arrangements(ins, ind, H, D, e, Ps, Pd, ls, ld):
 
 @pytest.mark.parametrize("launch", [dict(order=1), dict(order=2), dict(xcd_swizzle=1), dict(nontemporal=1),
                                     dict(nontemporal=2), dict(nontemporal=3), dict(nontemporal=3, order=2),
-                                    dict(max_workgroups=5), dict(order=2, max_workgroups=16)])
+                                    dict(max_workgroups=5), dict(order=2, max_workgroups=16), dict(order=3)])
 def test_inner_results_do_not_depend_on_launch_config(launch):
     rng = np.random.default_rng(12)
     case = G.make_case(rng, 2, 4, 64, 2, [300, 1, 77, 0, 64, 33], 32, 16, LM, PM, inner_s=ROWS, inner_d=SPLIT)

@@ -89,6 +89,8 @@ def test_explicit_strides_padded_rows_and_pages():
     dict(threads=64), dict(threads=128, unroll=2, xcd_swizzle=1), dict(threads=512, unroll=4, order=2),
     dict(threads=1024, unroll=8), dict(threads=1024, unroll=1, max_workgroups=16),
     dict(order=1), dict(order=2, xcd_swizzle=1), dict(order=2, threads=512, unroll=4),
+    dict(order=3), dict(order=3, xcd_swizzle=1, max_workgroups=37), dict(order=3, threads=512, unroll=2, nontemporal=3),
+    dict(order=3, xcd_block_tiles=64, max_workgroups=24),
     dict(threads=256, unroll=4, workgroups_per_cu=2), dict(threads=512, unroll=4, workgroups_per_cu=1),
     dict(nontemporal=3), dict(nontemporal=3, threads=512, unroll=4, order=2), dict(nontemporal=3, unroll=8),
     dict(nontemporal=2), dict(workgroups_per_cu=6), dict(xcd_block_tiles=8), dict(xcd_block_tiles=64, threads=64),

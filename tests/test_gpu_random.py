@@ -34,7 +34,7 @@ def draw_case(seed):
     l1 = int(rng.integers(l0, L + 1))
     launch = None
     if rng.random() < 0.6:
-        launch = dict(order=int(rng.integers(0, 3)), xcd_swizzle=int(rng.integers(1, 3)),
+        launch = dict(order=int(rng.integers(0, 4)), xcd_swizzle=int(rng.integers(1, 3)),
                       nontemporal=int(rng.integers(0, 4)), threads=int(rng.choice([0, 64, 128, 256, 512, 1024])),
                       unroll=int(rng.choice([0, 1, 2, 4, 8])), max_workgroups=int(rng.choice([0, 0, 3, 40, 1000])),
                       xcd_block_tiles=int(rng.choice([0, 0, 1, 4, 64])), workgroups_per_cu=int(rng.choice([0, 0, 2, 5])))
