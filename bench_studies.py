@@ -12,6 +12,8 @@
   ceilings the device's own limits for this kind of work, measured with two plain kernels that plan nothing:
            a contiguous copy, and the same copy cut into chunks that random permutations scatter on the
            source side (gather), the destination side (scatter) or both, over a sweep of chunk sizes
+  placement the same unpack and pack against several fresh allocations of the pool inside one process: how
+           much the rate of a small-chunk workload depends on the physical memory an allocation happens to get
   layouts  pools whose pages are head-major or keep the token axis inside 16-byte groups of the head
            dimension, against plain [token][head][dim] pages of the same shape
 """
@@ -294,6 +296,32 @@ def study_ceilings(args):
         print(json.dumps(row), flush=True)
 
 
+def study_placement(args):
+    import torch
+    s = bench.Setup(args.workload, fill=False)
+    kvx = s.kvx
+    p = s.plan()
+
+    def rate(ms):
+        return round(2 * s.payload / ms / 1e6, 1)
+    free, _ = torch.cuda.mem_get_info()
+    count = max(1, min(args.pools, int(0.9 * free) // s.dst.numel()))   # what fits beside the workload itself
+    for rnd in range(3):
+        pools = [torch.empty_like(s.dst) for _ in range(count)]
+        rows = []
+        for d in pools:
+            unpack_ms = s.time_op(lambda: kvx.kvx_unpack(p, s.buf.data_ptr(), s.payload, d.data_ptr(),
+                                                         s.stream.cuda_stream), iters=6, warmup=1)
+            pack_ms = s.time_op(lambda: kvx.kvx_pack(p, d.data_ptr(), s.buf.data_ptr(), s.payload,
+                                                     s.stream.cuda_stream), iters=6, warmup=1)
+            rows.append({"address_MiB": d.data_ptr() >> 20, "unpack_into_hbm_GBps": rate(unpack_ms),
+                         "pack_from_hbm_GBps": rate(pack_ms)})
+        print(json.dumps({"study": "placement", "workload": args.workload, "round": rnd, "pools": rows}), flush=True)
+        del pools, d
+        torch.cuda.empty_cache()
+    p.destroy()
+
+
 def study_slice(args):
     """A head slice of a wider sender pool (sender with all 8 KV heads, receiver holding heads [2,6)):
     the sender is described by explicit strides and a moved base pointer; rows are 1 KiB pieces at a
@@ -339,18 +367,19 @@ def study_slice(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval", "slice", "overlap", "ceilings"])
+    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval", "slice", "overlap", "ceilings", "placement"])
     ap.add_argument("--requests", type=int, default=512, help="retrieval: requests of the workload-5 shape")
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 5])
     ap.add_argument("--layers", type=int, default=8, help="blocks: layers of the workload-2 shape to move")
     ap.add_argument("--gib", type=int, default=4, help="ceilings: GiB copied per launch")
+    ap.add_argument("--pools", type=int, default=8, help="placement: fresh pool allocations per round")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench_studies.py: no GPU visible")
     {"blocks": study_blocks, "layers": study_layers, "layouts": study_layouts,
      "retrieval": study_retrieval, "slice": study_slice, "overlap": study_overlap,
-     "ceilings": study_ceilings}[args.study](args)
+     "ceilings": study_ceilings, "placement": study_placement}[args.study](args)
 
 
 if __name__ == "__main__":
