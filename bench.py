@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per copy_kernel launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by the plain-copy calibration), valid only for the kernel source they were taken on.
 COUNTER_RUNS = {
-    "kernels_sha256": "8c263f79743b9fb08232d9f521b9341e5f44fd8f24ea11d7197ebb9cf610b354",
-    "traffic_bytes_per_launch": {2: 12103875604, 3: 13228397731, 5: 47001472844, 4: 152992097585},
+    "kernels_sha256": "61e0fd0a6f3fd93f08cf57f6bf60b49d18bc39f528af99913d240eb633420d88",
+    "traffic_bytes_per_launch": {2: 12103884427, 3: 13228393373, 5: 47001462376, 4: 152991916435},
 }
 
 

@@ -273,6 +273,13 @@ def study_ceilings(args):
     t = timed(lambda: kvx.kvx_copy_yardstick(dst.data_ptr(), src.data_ptr(), nbytes, stream.cuda_stream))
     print(json.dumps({"study": "ceilings", "kernel": "plain_copy_kernel", "bytes": nbytes,
                       "ms": round(t, 4), "hbm_GBps": round(2 * nbytes / t / 1e6, 1)}), flush=True)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    t = timed(lambda: kvx.kvx_read_yardstick(src.data_ptr(), nbytes, sink.data_ptr(), stream.cuda_stream))
+    print(json.dumps({"study": "ceilings", "kernel": "read_only_kernel", "bytes": nbytes,
+                      "ms": round(t, 4), "hbm_GBps": round(nbytes / t / 1e6, 1)}), flush=True)
+    t = timed(lambda: kvx.kvx_write_yardstick(dst.data_ptr(), nbytes, 0x5A5A5A5A, stream.cuda_stream))
+    print(json.dumps({"study": "ceilings", "kernel": "write_only_kernel", "bytes": nbytes,
+                      "ms": round(t, 4), "hbm_GBps": round(nbytes / t / 1e6, 1)}), flush=True)
     with torch.cuda.stream(stream):
         t = timed(lambda: dst.copy_(src))
     print(json.dumps({"study": "ceilings", "kernel": "runtime device-to-device copy (torch copy_)", "bytes": nbytes,

@@ -344,6 +344,14 @@ kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const 
 kvx_status kvx_copy_yardstick_chunks(void *dst, const void *src, uint64_t bytes, uint32_t chunk_bytes,
                                      const uint32_t *src_perm, const uint32_t *dst_perm, void *stream);
 
+/* One-way yardsticks: read `bytes` (a multiple of 4096, at most 32 GiB) of buf [device, 16-byte aligned] and
+ * write nothing, or fill them with `word` and read nothing, in the data mover's default launch shape.  What the
+ * device's memory gives in one direction bounds what any copy can reach.  `sink` [device, 4 bytes] exists
+ * only so that the loads have a use; it is written if a 16-byte unit of the data matches one fixed pattern.
+ * Errors: KVX_ERR_INVALID_ARG, KVX_ERR_ALIGNMENT, KVX_ERR_UNSUPPORTED (too large), KVX_ERR_DEVICE. */
+kvx_status kvx_read_yardstick(const void *buf, uint64_t bytes, void *sink, void *stream);
+kvx_status kvx_write_yardstick(void *buf, uint64_t bytes, uint32_t word, void *stream);
+
 const char *kvx_status_string(kvx_status st);
 
 /* The hipError_t value behind this thread's most recent KVX_ERR_DEVICE (0 if none) and, through `where`

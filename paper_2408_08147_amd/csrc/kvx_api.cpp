@@ -846,6 +846,23 @@ kvx_status kvx_copy_yardstick_chunks(void *dst, const void *src, uint64_t bytes,
     return hip_ok(e, "chunk_copy_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
 }
 
+kvx_status kvx_read_yardstick(const void *buf, uint64_t bytes, void *sink, void *stream) {
+    if (!buf || !sink || bytes % 4096) return KVX_ERR_INVALID_ARG;
+    if ((uintptr_t)buf % 16 || (uintptr_t)sink % 4) return KVX_ERR_ALIGNMENT;
+    if (bytes / 4096 >= (1ull << 31) / 256) return KVX_ERR_UNSUPPORTED;
+    hipError_t e = launch_one_way(const_cast<char *>(static_cast<const char *>(buf)), bytes, false, 0,
+                                  static_cast<uint32_t *>(sink), static_cast<hipStream_t>(stream));
+    return hip_ok(e, "read_only_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
+}
+
+kvx_status kvx_write_yardstick(void *buf, uint64_t bytes, uint32_t word, void *stream) {
+    if (!buf || bytes % 4096) return KVX_ERR_INVALID_ARG;
+    if ((uintptr_t)buf % 16) return KVX_ERR_ALIGNMENT;
+    if (bytes / 4096 >= (1ull << 31) / 256) return KVX_ERR_UNSUPPORTED;
+    hipError_t e = launch_one_way(static_cast<char *>(buf), bytes, true, word, nullptr, static_cast<hipStream_t>(stream));
+    return hip_ok(e, "write_only_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
+}
+
 int kvx_last_device_error(const char **where) {
     if (where) *where = g_last_hip_where;
     return g_last_hip_error;

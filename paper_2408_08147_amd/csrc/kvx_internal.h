@@ -150,6 +150,8 @@ inline uint32_t occupancy_lds(uint32_t per_cu) { return per_cu ? kLdsPerCu / per
 hipError_t launch_plain_copy(char *dst, const char *src, uint64_t bytes, uint32_t threads, uint32_t unroll,
                              int nontemporal, uint32_t max_wg, hipStream_t stream);
 
+hipError_t launch_one_way(char *buf, uint64_t bytes, bool write, uint32_t word, uint32_t *sink, hipStream_t stream);
+
 hipError_t launch_chunk_copy(char *dst, const char *src, uint64_t bytes, uint32_t log2_tiles_per_chunk,
                              const uint32_t *src_perm, const uint32_t *dst_perm, hipStream_t stream);
 

@@ -483,6 +483,25 @@ __global__ __launch_bounds__(T) void plain_copy_kernel(const char *__restrict__ 
     }
 }
 
+// One-way yardsticks, one 4 KiB tile per workgroup like the data mover's default shape: only loads, or only
+// stores.  The loads feed a value that is stored if it matches a pattern no lane will ever compute, so the
+// compiler has to keep them while nothing is written.
+__global__ __launch_bounds__(256) void read_only_kernel(const char *__restrict__ src, uint32_t *__restrict__ sink,
+                                                        uint32_t total_tiles, uint32_t swizzle_chunk) {
+    const uint32_t b = (blockIdx.x & 7u) * swizzle_chunk + (blockIdx.x >> 3);
+    if (b >= total_tiles) return;
+    const u32x4 v = ld16<1>(src + (uint64_t)b * 4096u + threadIdx.x * 16u);
+    if ((v.x ^ v.y) == 0x9E3779B9u && (v.z ^ v.w) == 0x7F4A7C15u && v.x == 0x2545F491u) *sink = v.w;
+}
+
+__global__ __launch_bounds__(256) void write_only_kernel(char *__restrict__ dst, uint32_t word, uint32_t total_tiles,
+                                                         uint32_t swizzle_chunk) {
+    const uint32_t b = (blockIdx.x & 7u) * swizzle_chunk + (blockIdx.x >> 3);
+    if (b >= total_tiles) return;
+    const u32x4 v = {word, word, word, word};
+    st16<1>(dst + (uint64_t)b * 4096u + threadIdx.x * 16u, v);
+}
+
 // Second yardstick: chunk-permuted copy, one 4 KiB tile per workgroup, the data mover's default shape.
 __global__ __launch_bounds__(256) void chunk_copy_kernel(const uint32_t *__restrict__ src_perm,
                                                          const uint32_t *__restrict__ dst_perm,
@@ -634,6 +653,15 @@ hipError_t launch_xpose(const XposeParams &p, bool src_token_fast, bool dst_toke
                               : xpose_sd<true, false>(p, nontemporal, grid, stream);
     return dst_token_fast ? xpose_sd<false, true>(p, nontemporal, grid, stream)
                           : xpose_sd<false, false>(p, nontemporal, grid, stream);
+}
+
+hipError_t launch_one_way(char *buf, uint64_t bytes, bool write, uint32_t word, uint32_t *sink, hipStream_t stream) {
+    const uint32_t tiles = (uint32_t)(bytes / 4096);
+    if (tiles == 0) return hipSuccess;
+    const uint32_t grid = (tiles + 7u) / 8u * 8u;
+    if (write) KVX_LAUNCH(write_only_kernel, dim3(grid), dim3(256), 0, stream, buf, word, tiles, grid / 8u);
+    else KVX_LAUNCH(read_only_kernel, dim3(grid), dim3(256), 0, stream, buf, sink, tiles, grid / 8u);
+    return hipGetLastError();
 }
 
 hipError_t launch_chunk_copy(char *dst, const char *src, uint64_t bytes, uint32_t log2_tiles_per_chunk,

@@ -28,7 +28,8 @@ EXPORTS = (
     "kvx_unpack_layers", "kvx_convert_layers", "kvx_pack_blockwise", "kvx_copy_yardstick",
     "kvx_retriever_arena_bytes", "kvx_retriever_create", "kvx_retriever_destroy", "kvx_retriever_acquire",
     "kvx_retriever_scatter", "kvx_retriever_abandon", "kvx_retriever_poll", "kvx_retriever_drain",
-    "kvx_copy_yardstick_chunks", "kvx_status_string", "kvx_last_device_error",
+    "kvx_copy_yardstick_chunks", "kvx_read_yardstick", "kvx_write_yardstick", "kvx_status_string",
+    "kvx_last_device_error",
 )
 
 
@@ -162,6 +163,8 @@ def load():
     lib.kvx_retriever_drain.argtypes = [C.c_void_p]
     lib.kvx_copy_yardstick_chunks.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p,
                                               C.c_void_p, C.c_void_p]
+    lib.kvx_read_yardstick.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
+    lib.kvx_write_yardstick.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p]
     lib.kvx_copy_yardstick.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(LaunchCfg), C.c_void_p]
     for name in EXPORTS:
         if name not in ("kvx_status_string", "kvx_plan_destroy", "kvx_retriever_destroy", "kvx_last_device_error"):
@@ -388,6 +391,16 @@ def kvx_copy_yardstick_chunks(dst: int, src: int, nbytes: int, chunk_bytes: int,
     _check(load().kvx_copy_yardstick_chunks(C.c_void_p(dst or None), C.c_void_p(src or None), nbytes, chunk_bytes,
                                             C.c_void_p(src_perm or None), C.c_void_p(dst_perm or None),
                                             C.c_void_p(stream or None)), "kvx_copy_yardstick_chunks")
+
+
+def kvx_read_yardstick(buf: int, nbytes: int, sink: int, stream: int = 0) -> None:
+    _check(load().kvx_read_yardstick(C.c_void_p(buf or None), nbytes, C.c_void_p(sink or None),
+                                     C.c_void_p(stream or None)), "kvx_read_yardstick")
+
+
+def kvx_write_yardstick(buf: int, nbytes: int, word: int, stream: int = 0) -> None:
+    _check(load().kvx_write_yardstick(C.c_void_p(buf or None), nbytes, word, C.c_void_p(stream or None)),
+           "kvx_write_yardstick")
 
 
 def pool_desc(num_layers: int, num_kv_heads: int, head_dim: int, elem_bytes: int, page_tokens: int,

@@ -60,3 +60,34 @@ def test_plain_yardstick_copies(nbytes):
     stream.synchronize()
     assert torch.equal(dst_t[:nbytes], src_t)
     assert bool((dst_t[nbytes:] == 0xEE).all())
+
+
+@pytest.mark.gpu
+def test_one_way_yardsticks():
+    import torch
+    dev = torch.device("cuda:0")
+    n = 37 * 4096
+    stream = torch.cuda.Stream(device=dev)
+    with torch.cuda.stream(stream):
+        buf = torch.full((n + 4096,), 0xEE, dtype=torch.uint8, device=dev)
+        kvx.kvx_write_yardstick(buf.data_ptr(), n, 0x01020304, stream.cuda_stream)
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        kvx.kvx_read_yardstick(buf.data_ptr(), n, sink.data_ptr(), stream.cuda_stream)
+    stream.synchronize()
+    got = buf.cpu().numpy()
+    assert np.array_equal(got[:n].view("<u4"), np.full(n // 4, 0x01020304, dtype="<u4"))
+    assert (got[n:] == 0xEE).all()
+    assert int(sink.item()) == 0
+
+
+def test_one_way_yardstick_argument_errors():
+    for fn, args, code in ((kvx.kvx_write_yardstick, (0, 4096, 1), kvx.ERR_INVALID_ARG),
+                           (kvx.kvx_write_yardstick, (4096, 4095, 1), kvx.ERR_INVALID_ARG),
+                           (kvx.kvx_write_yardstick, (4096 + 4, 4096, 1), kvx.ERR_ALIGNMENT),
+                           (kvx.kvx_write_yardstick, (4096, 1 << 36, 1), kvx.ERR_UNSUPPORTED),
+                           (kvx.kvx_read_yardstick, (4096, 4096, 0), kvx.ERR_INVALID_ARG),
+                           (kvx.kvx_read_yardstick, (0, 4096, 64), kvx.ERR_INVALID_ARG),
+                           (kvx.kvx_read_yardstick, (4096, 4096, 66), kvx.ERR_ALIGNMENT)):
+        with pytest.raises(kvx.KvxError) as ei:
+            fn(*args)
+        assert ei.value.status == code, (fn.__name__, args)
