@@ -41,7 +41,7 @@ def draw_case(seed):
     return case, (l0, l1), launch, rng
 
 
-@pytest.mark.parametrize("seed", range(1000, 1060))
+@pytest.mark.parametrize("seed", range(1000, 1300))
 def test_random_case(seed):
     case, (l0, l1), launch, rng = draw_case(seed)
     src = rng.integers(0, 256, size=case.pool_bytes(case.s), dtype=np.uint8)
