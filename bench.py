@@ -204,6 +204,7 @@ def main():
     ms_step = (t1 - t0) * 1e3 / K
     pack_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / K
     unpack_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / K
+    per_step = sorted(e[0].elapsed_time(e[2]) for e in evs)   # the launches of one step, plan kernels excluded
 
     # outside the step: plan alone (host + device part), convert pool to pool, plain D2D copy ceiling
     t2 = time.perf_counter()
@@ -244,6 +245,8 @@ def main():
         "hbm_frac_step": round(traffic_per_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "us_per_request": round(ms_step * 1e3 / R, 2), "requests_per_s": round(R / (ms_step * 1e-3), 1),
         "ops": {"plan_ms": round(plan_ms, 4),
+                "step_kernels_ms_median": round(per_step[len(per_step) // 2], 4),
+                "step_kernels_ms_min": round(per_step[0], 4),
                 "pack_ms": None if convert_only else round(pack_ms, 4),
                 "unpack_ms": None if convert_only else round(unpack_ms, 4),
                 "convert_ms": round(convert_ms, 4),
