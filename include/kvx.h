@@ -135,8 +135,9 @@ typedef struct {
                                each, or blocks of `xcd_block_tiles` tiles dealt round-robin */
     uint32_t max_workgroups;/* cap on the grid; tiles beyond it are taken in a grid-stride loop */
     uint32_t threads;       /* lanes per workgroup: 64, 128, 256, 512 or 1024; a tile is threads*16*unroll bytes */
-    uint32_t workgroups_per_cu; /* 0 = as many as fit; n = at most n resident per compute unit (1..8), which
-                               bounds the bytes in flight; done by reserving unused LDS per workgroup */
+    uint32_t workgroups_per_cu; /* 0 = as many as fit (with the library's own 32 KiB tiles of order 2: one);
+                               n = at most n resident per compute unit (1..8), which bounds the bytes in
+                               flight; done by reserving unused LDS per workgroup */
     uint32_t xcd_block_tiles; /* with xcd_swizzle 2: 0 = eighths of the grid, else a power of two */
 } kvx_launch_cfg;
 
