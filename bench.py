@@ -24,8 +24,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per copy_kernel launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (scaled by the plain-copy calibration), valid only for the kernel source they were taken on.
 COUNTER_RUNS = {
-    "kernels_sha256": "61e0fd0a6f3fd93f08cf57f6bf60b49d18bc39f528af99913d240eb633420d88",
-    "traffic_bytes_per_launch": {2: 12103884427, 3: 13228393373, 5: 47001462376, 4: 152991916435},
+    "kernels_sha256": "55c678666db740a217bce1c13d1caedc45b10c511eb3b384f158e064a6d44cab",
+    "traffic_bytes_per_launch": {2: 12103884171, 3: 13228392986, 5: 47001490184, 4: 153000252854},
 }
 
 

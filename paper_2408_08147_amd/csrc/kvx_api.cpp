@@ -52,15 +52,20 @@ struct PinnedBlock {
     void *ptr = nullptr;
     size_t bytes = 0;
     hipEvent_t copied = nullptr;
+    int device = -1; // the event belongs to this device: a block serves plans of that device only
 };
 std::mutex g_pinned_mu;
 std::vector<PinnedBlock> g_pinned_free;
 
 hipError_t pinned_acquire(size_t bytes, PinnedBlock *out) {
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
     {
         std::lock_guard<std::mutex> lk(g_pinned_mu);
         for (size_t i = 0; i < g_pinned_free.size(); ++i) {
-            if (g_pinned_free[i].bytes >= bytes && g_pinned_free[i].bytes <= 4 * bytes + 4096 &&
+            if (g_pinned_free[i].device == device && g_pinned_free[i].bytes >= bytes &&
+                g_pinned_free[i].bytes <= 4 * bytes + 4096 &&
                 hipEventQuery(g_pinned_free[i].copied) == hipSuccess) {
                 *out = g_pinned_free[i];
                 g_pinned_free.erase(g_pinned_free.begin() + i);
@@ -70,7 +75,7 @@ hipError_t pinned_acquire(size_t bytes, PinnedBlock *out) {
     }
     size_t cap = std::max<size_t>(align_up(bytes, 4096), 4096);
     void *p = nullptr;
-    hipError_t e = hipHostMalloc(&p, cap, hipHostMallocDefault);
+    e = hipHostMalloc(&p, cap, hipHostMallocDefault);
     if (e != hipSuccess) return e;
     hipEvent_t ev = nullptr;
     e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
@@ -81,6 +86,7 @@ hipError_t pinned_acquire(size_t bytes, PinnedBlock *out) {
     out->ptr = p;
     out->bytes = cap;
     out->copied = ev;
+    out->device = device;
     return hipSuccess;
 }
 

@@ -23,6 +23,7 @@
 //                LDS when one side is contiguous along the row and the other
 //                along the tokens.
 #include <algorithm>
+#include <atomic>
 
 #include "kvx_internal.h"
 
@@ -561,12 +562,17 @@ namespace {
 template <int T, int U, int NT>
 hipError_t copy_tun(const CopyParams &p, uint32_t grid, uint32_t lds, hipStream_t stream) {
     if (lds > 64u * 1024u) {
-        static bool raised = false; // per instantiation; the attribute is sticky
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&copy_kernel<T, U, NT>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
+        // The attribute is sticky, per kernel instance and per device: remember where it has been raised.
+        static std::atomic<uint64_t> raised_on{0};
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        const uint64_t bit = dev >= 0 && dev < 64 ? 1ull << dev : 0;
+        if (!(raised_on.load(std::memory_order_relaxed) & bit) || !bit) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&copy_kernel<T, U, NT>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
             if (e != hipSuccess) return e;
-            raised = true;
+            raised_on.fetch_or(bit, std::memory_order_relaxed);
         }
     }
     KVX_LAUNCH((copy_kernel<T, U, NT>), dim3(grid), dim3(T), lds, stream, p.runs, p.src, p.dst, p);
