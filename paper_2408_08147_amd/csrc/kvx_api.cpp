@@ -457,7 +457,7 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
         const uint64_t table_words = (uint64_t)R + ids_s.size() + ids_d.size();
         const bool tables_inline = table_words <= kInlineWords;
         bool ok = true;
-        InlineTables it;
+        InlineTables it{}; // zeroed: the whole struct travels as a launch argument
         if (tables_inline) {
             const uint32_t *seg[3] = {p->seq_lens.data(), ids_s.data(), ids_d.data()};
             const uint64_t off[3] = {z.off_lens, z.off_ids_s, z.off_ids_d};
