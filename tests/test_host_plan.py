@@ -3,6 +3,7 @@ and the host side of kvx_plan (validation, sizes, segments) behaves as
 include/kvx.h states.  No kernel is launched: plans are host-only."""
 import os
 import re
+import subprocess
 
 import numpy as np
 import pytest
@@ -209,3 +210,14 @@ def test_retriever_sizing_errors():
         with pytest.raises(kvx.KvxError) as ei:
             kvx.kvx_retriever_arena_bytes(*args)
         assert ei.value.status == code, args
+
+
+def test_public_header_is_plain_c99_and_cxx17(tmp_path):
+    """include/kvx.h on its own, pedantic and warning-free, as C99 and as C++17."""
+    inc = os.path.join(ROOT, "include")
+    for compiler, std, ext in (("gcc", "-std=c99", "c"), ("g++", "-std=c++17", "cpp")):
+        src = tmp_path / f"only_header.{ext}"
+        src.write_text('#include "kvx.h"\nint main(void) { return (int)sizeof(kvx_run) - 32; }\n')
+        res = subprocess.run([compiler, std, "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", inc, "-c", str(src),
+                              "-o", str(tmp_path / f"only_header_{ext}.o")], capture_output=True, text=True)
+        assert res.returncode == 0, res.stderr[-2000:]
