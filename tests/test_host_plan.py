@@ -221,3 +221,25 @@ def test_public_header_is_plain_c99_and_cxx17(tmp_path):
         res = subprocess.run([compiler, std, "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", inc, "-c", str(src),
                               "-o", str(tmp_path / f"only_header_{ext}.o")], capture_output=True, text=True)
         assert res.returncode == 0, res.stderr[-2000:]
+
+
+def test_no_library_no_result(monkeypatch, tmp_path):
+    """Without the HIP library every entry point of the binding raises: there is no other path to fall back to."""
+    from paper_2408_08147_amd import build as B
+
+    def no_compiler():
+        raise RuntimeError("hipcc is not here")
+    monkeypatch.setattr(kvx, "_lib", None)
+    monkeypatch.setattr(B, "LIB", str(tmp_path / "libkvx_absent.so"))
+    monkeypatch.setattr(B, "build", no_compiler)
+    sp, sb = _simple()
+    with pytest.raises(RuntimeError, match="hipcc is not here"):
+        kvx.kvx_plan_workspace_bytes(sp, sb, None, None)
+    with pytest.raises(RuntimeError, match="hipcc is not here"):
+        kvx.kvx_plan(sp, sb, None, None, 0, 2)
+    # a file that is not a loadable library fails just as loudly
+    bad = tmp_path / "libkvx_broken.so"
+    bad.write_bytes(b"not an ELF file")
+    monkeypatch.setattr(B, "LIB", str(bad))
+    with pytest.raises(OSError):
+        kvx.kvx_plan_workspace_bytes(sp, sb, None, None)
