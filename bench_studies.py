@@ -12,6 +12,8 @@
   ceilings the device's own limits for this kind of work, measured with two plain kernels that plan nothing:
            a contiguous copy, and the same copy cut into chunks that random permutations scatter on the
            source side (gather), the destination side (scatter) or both, over a sweep of chunk sizes
+  knobs    every launch knob against the defaults inside ONE process, on the same allocations (comparisons across
+           processes are blurred by where the allocations happen to land, see placement)
   placement the same unpack and pack against several fresh allocations of the pool inside one process: how
            much the rate of a small-chunk workload depends on the physical memory an allocation happens to get
   layouts  pools whose pages are head-major or keep the token axis inside 16-byte groups of the head
@@ -303,6 +305,36 @@ def study_ceilings(args):
         print(json.dumps(row), flush=True)
 
 
+def study_knobs(args):
+    s = bench.Setup(args.workload, fill=False)
+    kvx = s.kvx
+    p = s.plan()
+    settings = [("defaults", {}),
+                ("xcd_swizzle off", dict(xcd_swizzle=1)),
+                ("xcd blocks of 1 tile", dict(xcd_block_tiles=1)), ("xcd blocks of 8", dict(xcd_block_tiles=8)),
+                ("xcd blocks of 64", dict(xcd_block_tiles=64)), ("xcd blocks of 512", dict(xcd_block_tiles=512)),
+                ("xcd blocks of 4096", dict(xcd_block_tiles=4096)),
+                ("order 1", dict(order=1)), ("order 2", dict(order=2)), ("order 3", dict(order=3)),
+                ("128 lanes", dict(threads=128)), ("512 lanes", dict(threads=512)), ("1024 lanes", dict(threads=1024)),
+                ("unroll 2", dict(unroll=2)), ("unroll 4", dict(unroll=4)), ("512 lanes, unroll 2", dict(threads=512, unroll=2)),
+                ("default cache policy", dict(nontemporal=1)), ("non-temporal", dict(nontemporal=2)),
+                ("non-temporal loads, agent-scope stores", dict(nontemporal=3)),
+                ("2 workgroups per CU", dict(workgroups_per_cu=2)), ("4 workgroups per CU", dict(workgroups_per_cu=4)),
+                ("6 workgroups per CU", dict(workgroups_per_cu=6)),
+                ("defaults again", {})]
+
+    def rate(ms):
+        return round(2 * s.payload / ms / 1e6, 1)
+    for name, cfg in settings:
+        kvx.kvx_plan_set_launch(p, **cfg)
+        tp = s.time_op(lambda: s.pack(p), iters=6, warmup=1)
+        tu = s.time_op(lambda: s.unpack(p), iters=6, warmup=1)
+        tc = s.time_op(lambda: s.convert(p), iters=6, warmup=1)
+        print(json.dumps({"study": "knobs", "workload": args.workload, "setting": name, "pack_hbm_GBps": rate(tp),
+                          "unpack_hbm_GBps": rate(tu), "convert_hbm_GBps": rate(tc)}), flush=True)
+    p.destroy()
+
+
 def study_placement(args):
     import torch
     s = bench.Setup(args.workload, fill=False)
@@ -374,7 +406,7 @@ def study_slice(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval", "slice", "overlap", "ceilings", "placement"])
+    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval", "slice", "overlap", "ceilings", "placement", "knobs"])
     ap.add_argument("--requests", type=int, default=512, help="retrieval: requests of the workload-5 shape")
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 5])
     ap.add_argument("--layers", type=int, default=8, help="blocks: layers of the workload-2 shape to move")
@@ -386,7 +418,7 @@ def main():
         sys.exit("bench_studies.py: no GPU visible")
     {"blocks": study_blocks, "layers": study_layers, "layouts": study_layouts,
      "retrieval": study_retrieval, "slice": study_slice, "overlap": study_overlap,
-     "ceilings": study_ceilings, "placement": study_placement}[args.study](args)
+     "ceilings": study_ceilings, "placement": study_placement, "knobs": study_knobs}[args.study](args)
 
 
 if __name__ == "__main__":
