@@ -256,6 +256,21 @@ def test_single_request_two_sided_plans(lens, Ps, Pd):
     check(case, lens[0] + Pd)
 
 
+def test_many_requests_whose_tables_still_fit_the_launch_arguments():
+    """600 requests, 140 of them non-empty with one page each: 600 + 140 + 140 words ride in the launch
+    arguments, and the scan runs with ten waves."""
+    rng = np.random.default_rng(880)
+    lens = np.zeros(600, dtype=np.uint32)
+    lens[rng.choice(600, size=140, replace=False)] = rng.integers(1, 17, size=140)
+    case = G.make_case(rng, 2, 2, 16, 2, lens, 16, 16, LM, PM)
+    assert len(lens) + len(case.ids_s) + len(case.ids_d) == 880
+    src = rng.integers(0, 256, size=case.pool_bytes(case.s), dtype=np.uint8)
+    want = G.run_oracle(case, src, 0, 2)
+    got = G.run_gpu(case, src, 0, 2, want_tables=True)
+    G.assert_same(got, want, "600 requests inline")
+    assert np.array_equal(got.extra["token_prefix"], np.concatenate([[0], np.cumsum(lens.astype(np.uint64))]))
+
+
 def test_plan_reuse_and_immediate_destroy():
     """A plan can be used many times, and destroyed right after enqueueing."""
     import torch
