@@ -1,13 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the block-free KV transfer hot path on one MI355X.
 
-One step = build the copy plan (kvx_plan: host validation, one H2D copy, scan
-and fill kernels), gather the batch's KV out of the sender's paged pool into
-the contiguous buffer (kvx_pack), scatter it into the receiver's paged pool
-(kvx_unpack).  Inputs are resident in HBM before the timed region.  Prints ONE
-JSON line.  Synthetic workload 2 (Llama-3-8B-shaped KV, 16 requests of
-1024..4096 tokens, 128-token pages, scattered block tables) unless --workload
-says otherwise.
+One step = build the copy plan (kvx_plan: host validation, then the scan and
+fill kernels, the lengths and block tables riding in the first one's launch
+arguments or, for batches too large for that, in one H2D copy before it),
+gather the batch's KV out of the sender's paged pool into the contiguous buffer
+(kvx_pack), scatter it into the receiver's paged pool (kvx_unpack).  Inputs are
+resident in HBM before the timed region.  Prints ONE JSON line.  The headline
+is synthetic workload 2 (Llama-3-8B-shaped KV, 16 requests of 1024..4096
+tokens, 128-token pages, scattered block tables) unless --workload says
+otherwise; the other full-size workloads (3, 5, and 4 whose step is kvx_plan +
+kvx_convert) follow under "other_workloads", each measured the same way, each
+with its own roofline and CPU-oracle figures.
 """
 import argparse
 import json
@@ -22,22 +26,23 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 
 # HBM bytes per copy_kernel launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
-# profiles/ (scaled by the plain-copy calibration), valid only for the kernel source they were taken on.
+# profiles/ (scaled by the plain-copy calibration).  They are figures of an earlier run, not of this one, and
+# are reported only while the library that runs is built from the very sources they were taken on.
 COUNTER_RUNS = {
-    "kernels_sha256": "55c678666db740a217bce1c13d1caedc45b10c511eb3b384f158e064a6d44cab",
-    "traffic_bytes_per_launch": {2: 12103884171, 3: 13228392986, 5: 47001490184, 4: 153000252854},
+    "build_id": "",
+    "summary": "profiles/copy_kernel_workloads_2_3_5_4.txt",
+    "traffic_bytes_per_launch": {},
 }
 
 
 def measured_traffic(workload: int):
-    import hashlib
+    """(bytes per launch, where the figure comes from), or (None, None)."""
+    from paper_2408_08147_amd import kvx
     if workload not in COUNTER_RUNS["traffic_bytes_per_launch"]:
-        return None
-    src = os.path.join(ROOT, "paper_2408_08147_amd", "csrc", "kvx_kernels.hip")
-    with open(src, "rb") as f:
-        if hashlib.sha256(f.read()).hexdigest() != COUNTER_RUNS["kernels_sha256"]:
-            return None  # the kernel changed since the counters were taken
-    return COUNTER_RUNS["traffic_bytes_per_launch"][workload]
+        return None, None
+    if kvx.kvx_build_id() != COUNTER_RUNS["build_id"]:
+        return None, None  # the library changed since the counters were taken
+    return COUNTER_RUNS["traffic_bytes_per_launch"][workload], COUNTER_RUNS["summary"]
 
 
 class Setup:
@@ -100,81 +105,85 @@ class Setup:
         return e0.elapsed_time(e1) / iters
 
 
-def cpu_baseline(setup: Setup, target_bytes: float = 1.5e9):
-    """Times the CPU oracle (pack + unpack) on the first few layers of the same
-    workload, copied off the device, and checks the GPU result against it."""
+def first_layers(t, w, num_pages, page, layout, layers):
+    """The first `layers` layers of a dense pool tensor, laid out as a pool of that many layers."""
+    row = w.row_bytes
+    if layout == 0:  # layer-major: a leading slice
+        return t[: layers * 2 * num_pages * page * row]
+    return t.view(num_pages, w.num_layers, 2 * page * row)[:, :layers].contiguous().view(-1)
+
+
+def cpu_baseline(setup: Setup, convert_only: bool, target_bytes: float = 1.5e9):
+    """Times the CPU oracle on the first few layers of the same workload, copied off the device (pack +
+    unpack, or convert for the conversion workload), and checks the GPU result for those layers against it."""
     import numpy as np
     from oracle import kvxo
     w, b = setup.w, setup.batch
     per_layer = 2 * w.row_bytes * b.total_tokens
     layers = int(max(1, min(w.num_layers, target_bytes // per_layer)))
-    assert w.layout_s == 0 and w.layout_d == 0, "sample by leading layers needs layer-major pools"
-    slab_s = 2 * b.num_pages_s * w.page_s * w.row_bytes
-    slab_d = 2 * b.num_pages_d * w.page_d * w.row_bytes
-    src = setup.src[: layers * slab_s].cpu().numpy()
-    ps = kvxo.Pool(layers, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_s, b.num_pages_s, 0)
-    pd = kvxo.Pool(layers, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_d, b.num_pages_d, 0)
+    src = first_layers(setup.src, w, b.num_pages_s, w.page_s, w.layout_s, layers).cpu().numpy()
+    ps = kvxo.Pool(layers, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_s, b.num_pages_s, w.layout_s)
+    pd = kvxo.Pool(layers, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_d, b.num_pages_d, w.layout_d)
     bs, bd = kvxo.Batch(b.seq_lens, b.ids_s, b.offs_s), kvxo.Batch(b.seq_lens, b.ids_d, b.offs_d)
     total = kvxo.total_bytes(ps, bs, 0, layers)
     cores = len(os.sched_getaffinity(0))
     cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
     out = {}
-    buf = np.empty(total, dtype=np.uint8)
-    dst = np.full(layers * slab_d, 0xC3, dtype=np.uint8)
+    buf = None if convert_only else np.empty(total, dtype=np.uint8)
+    dst = np.full(pd.nbytes, 0xC3, dtype=np.uint8)
     for label, th in (("threads_1", 1), ("all", cores)):
-        buf[:] = 0
         t0 = time.perf_counter()
-        kvxo.pack(ps, bs, 0, layers, src, buf, threads=th)
-        t1 = time.perf_counter()
-        kvxo.unpack(pd, bd, 0, layers, buf, dst, threads=th)
-        t2 = time.perf_counter()
-        out[label] = dict(pack_s=t1 - t0, unpack_s=t2 - t1, gbps=2 * total / (t2 - t0) / 1e9)
-    # bonus parity at full shape: the GPU's result for these layers, through its own full-range plan
+        if convert_only:
+            kvxo.convert(ps, bs, pd, bd, 0, layers, src, dst, threads=th)
+            t1 = t2 = time.perf_counter()
+            moved = total
+        else:
+            kvxo.pack(ps, bs, 0, layers, src, buf, threads=th)
+            t1 = time.perf_counter()
+            kvxo.unpack(pd, bd, 0, layers, buf, dst, threads=th)
+            t2 = time.perf_counter()
+            moved = 2 * total
+        out[label] = dict(first_s=t1 - t0, second_s=t2 - t1, gbps=moved / (t2 - t0) / 1e9)
+    # parity at full shape on the sample: the GPU's result for these layers, through its own full-range plan
     plan = setup.plan()
     with setup.torch.cuda.stream(setup.stream):
         setup.dst.fill_(0xC3)
-    setup.pack(plan)
-    setup.unpack(plan)
+    if convert_only:
+        setup.convert(plan)
+    else:
+        setup.pack(plan)
+        setup.unpack(plan)
     setup.stream.synchronize()
-    got_dst = setup.dst[: layers * slab_d].cpu().numpy()
+    got_dst = first_layers(setup.dst, w, b.num_pages_d, w.page_d, w.layout_d, layers).cpu().numpy()
     ok = bool(np.array_equal(got_dst, dst))
-    gbuf = setup.buf.cpu().numpy()
-    for r in range(w.num_requests):
-        for l in (0, layers - 1):
-            o, n = setup.kvx.kvx_plan_segment(plan, r, l)
-            oo, nn = kvxo.segment(ps, bs, 0, layers, r, l)
-            ok = ok and n == nn and bool(np.array_equal(gbuf[o:o + n], buf[oo:oo + nn]))
+    if not convert_only:
+        gbuf = setup.buf.cpu().numpy()
+        for r in range(w.num_requests):
+            for l in (0, layers - 1):
+                o, n = setup.kvx.kvx_plan_segment(plan, r, l)
+                oo, nn = kvxo.segment(ps, bs, 0, layers, r, l)
+                ok = ok and n == nn and bool(np.array_equal(gbuf[o:o + n], buf[oo:oo + nn]))
     plan.destroy()
+    both = out["all"]["first_s"] + out["all"]["second_s"]
+    what = "convert" if convert_only else "pack+unpack"
     return {
         "value": round(out["all"]["gbps"], 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
-        "sample": f"pack+unpack of layers [0,{layers}) of the same batch ({total / 1e9:.2f} GB payload), "
-                  f"moved bytes = 2*payload",
+        "sample": f"{what} of layers [0,{layers}) of the same batch ({total / 1e9:.2f} GB payload), "
+                  f"moved bytes = {'payload' if convert_only else '2*payload'}; value is measured on the sample, "
+                  f"us_per_request is the sample's time scaled to all {w.num_layers} layers",
+        "extrapolated_from_layers": layers, "of_layers": w.num_layers,
         "value_1_thread": round(out["threads_1"]["gbps"], 3),
-        "us_per_request": round((out["all"]["pack_s"] + out["all"]["unpack_s"]) * 1e6 / w.num_requests
-                                * (w.num_layers / layers), 1),
+        "us_per_request": round(both * 1e6 / w.num_requests * (w.num_layers / layers), 1),
         "gpu_matches_oracle_on_sample": ok,
     }
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5],
-                    help="4 = page-size/layout conversion: the step is kvx_plan + kvx_convert")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this path runs on one GPU (no collectives, no sharding); use --gpus 1")
-
+def measure(workload: int, K: int, Wm: int, with_cpu: bool):
+    """Times K steps of one workload after Wm warm-up steps; returns the fields of its report."""
     import torch
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
-    convert_only = args.workload == 4
-    s = Setup(args.workload, with_buf=not convert_only)
+    convert_only = workload == 4
+    s = Setup(workload, with_buf=not convert_only)
     kvx, w = s.kvx, s.w
-    K, Wm = args.steps, args.warmup
 
     def step(events=None):
         p = s.plan()
@@ -233,11 +242,9 @@ def main():
         traffic_per_step = 4 * s.payload
     achieved = 2 * s.payload / (dom_ms * 1e-3) / 1e9
     R = w.num_requests
+    traffic, traffic_from = measured_traffic(workload)
     out = {
-        "metric": "kv_pack_unpack_moved", "value": round(moved, 1), "unit": "GB/s",
-        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u8", "data": "synthetic",
+        "value": round(moved, 1), "unit": "GB/s", "steps": K, "warmup": Wm, "ms_per_step": round(ms_step, 4),
         "config": {"workload": f"{s.w.index}:{w.name}", "layers": w.num_layers, "kv_heads": w.num_kv_heads,
                    "head_dim": w.head_dim, "elem_bytes": w.elem_bytes, "page_tokens": w.page_s,
                    "requests": R, "total_tokens": s.batch.total_tokens, "payload_bytes": s.payload,
@@ -258,10 +265,47 @@ def main():
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_launch": 2 * s.payload,
-                     "traffic": measured_traffic(args.workload)},
+                     "traffic": traffic, "traffic_from": traffic_from},
     }
-    if not args.no_cpu_baseline and not convert_only:
-        out["cpu_baseline"] = cpu_baseline(s)
+    if with_cpu:
+        out["cpu_baseline"] = cpu_baseline(s, convert_only)
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5],
+                    help="4 = page-size/layout conversion: the step is kvx_plan + kvx_convert")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="only the headline workload (profiling runs use this)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this path runs on one GPU (no collectives, no sharding); use --gpus 1")
+
+    import gc
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    head = measure(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+    out = {"metric": "kv_pack_unpack_moved", "value": head.pop("value"), "unit": head.pop("unit"),
+           "n_gpus": 1, "steps": head.pop("steps"), "warmup": head.pop("warmup"),
+           "ms_per_step": head.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "u8", "data": "synthetic"}
+    out.update(head)
+    if not args.no_other_workloads:
+        # the other full-size workloads, each a short run of the same kind: same fields, one entry each
+        out["other_workloads"] = []
+        for idx in (3, 5, 4):
+            if idx == args.workload:
+                continue
+            gc.collect()
+            torch.cuda.empty_cache()
+            out["other_workloads"].append(measure(idx, max(args.steps, 20) if idx != 4 else args.steps,
+                                                  args.warmup, not args.no_cpu_baseline))
     print(json.dumps(out))
 
 

@@ -9,13 +9,6 @@
   retrieval asynchronous retrieval (section 3.6): requests arriving one by one through k receive slots
   overlap  RecvScatter beside a stand-in for the running model (GEMMs on another stream), grid capped or not
   slice    a head slice of a wider sender pool through explicit strides (unequal tensor-parallel degrees)
-  ceilings the device's own limits for this kind of work, measured with two plain kernels that plan nothing:
-           a contiguous copy, and the same copy cut into chunks that random permutations scatter on the
-           source side (gather), the destination side (scatter) or both, over a sweep of chunk sizes
-  knobs    every launch knob against the defaults inside ONE process, on the same allocations (comparisons across
-           processes are blurred by where the allocations happen to land, see placement)
-  placement the same unpack and pack against several fresh allocations of the pool inside one process: how
-           much the rate of a small-chunk workload depends on the physical memory an allocation happens to get
   layouts  pools whose pages are head-major or keep the token axis inside 16-byte groups of the head
            dimension, against plain [token][head][dim] pages of the same shape
 """
@@ -247,120 +240,6 @@ def study_overlap(args):
     p.destroy()
 
 
-def study_ceilings(args):
-    import numpy as np
-    import torch
-    from paper_2408_08147_amd import kvx
-    dev = torch.device("cuda:0")
-    stream = torch.cuda.Stream(device=dev)
-    nbytes = args.gib << 30
-    rng = np.random.default_rng(240808147)
-    with torch.cuda.stream(stream):
-        src = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-        dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-        src.random_(0, 256)
-        dst.zero_()
-
-    def timed(fn, iters=10, warmup=2):
-        for _ in range(warmup):
-            fn()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for _ in range(iters):
-            fn()
-        e1.record(stream)
-        e1.synchronize()
-        return e0.elapsed_time(e1) / iters
-
-    t = timed(lambda: kvx.kvx_copy_yardstick(dst.data_ptr(), src.data_ptr(), nbytes, stream.cuda_stream))
-    print(json.dumps({"study": "ceilings", "kernel": "plain_copy_kernel", "bytes": nbytes,
-                      "ms": round(t, 4), "hbm_GBps": round(2 * nbytes / t / 1e6, 1)}), flush=True)
-    sink = torch.zeros(1, dtype=torch.int32, device=dev)
-    t = timed(lambda: kvx.kvx_read_yardstick(src.data_ptr(), nbytes, sink.data_ptr(), stream.cuda_stream))
-    print(json.dumps({"study": "ceilings", "kernel": "read_only_kernel", "bytes": nbytes,
-                      "ms": round(t, 4), "hbm_GBps": round(nbytes / t / 1e6, 1)}), flush=True)
-    t = timed(lambda: kvx.kvx_write_yardstick(dst.data_ptr(), nbytes, 0x5A5A5A5A, stream.cuda_stream))
-    print(json.dumps({"study": "ceilings", "kernel": "write_only_kernel", "bytes": nbytes,
-                      "ms": round(t, 4), "hbm_GBps": round(nbytes / t / 1e6, 1)}), flush=True)
-    with torch.cuda.stream(stream):
-        t = timed(lambda: dst.copy_(src))
-    print(json.dumps({"study": "ceilings", "kernel": "runtime device-to-device copy (torch copy_)", "bytes": nbytes,
-                      "ms": round(t, 4), "hbm_GBps": round(2 * nbytes / t / 1e6, 1)}), flush=True)
-    for chunk in (4096, 8192, 16384, 32768, 65536, 131072, 262144, 1048576, 4194304):
-        n = nbytes // chunk
-        with torch.cuda.stream(stream):
-            ps = torch.from_numpy(rng.permutation(n).astype(np.uint32)).to(dev)
-            pd = torch.from_numpy(rng.permutation(n).astype(np.uint32)).to(dev)
-        row = {"study": "ceilings", "kernel": "chunk_copy_kernel", "bytes": nbytes, "chunk_bytes": chunk}
-        for name, a, b in (("identity", 0, 0), ("gather", ps.data_ptr(), 0), ("scatter", 0, pd.data_ptr()),
-                           ("both", ps.data_ptr(), pd.data_ptr())):
-            t = timed(lambda: kvx.kvx_copy_yardstick_chunks(dst.data_ptr(), src.data_ptr(), nbytes, chunk, a, b,
-                                                            stream.cuda_stream))
-            row[name + "_hbm_GBps"] = round(2 * nbytes / t / 1e6, 1)
-        # the last pass (both permutations) must have produced the permuted copy
-        stream.synchronize()
-        k = int(rng.integers(0, n))
-        lo_d, lo_s = int(pd[k]) * chunk, int(ps[k]) * chunk
-        row["spot_check_ok"] = bool(torch.equal(dst[lo_d:lo_d + chunk], src[lo_s:lo_s + chunk]))
-        print(json.dumps(row), flush=True)
-
-
-def study_knobs(args):
-    s = bench.Setup(args.workload, fill=False)
-    kvx = s.kvx
-    p = s.plan()
-    settings = [("defaults", {}),
-                ("xcd_swizzle off", dict(xcd_swizzle=1)),
-                ("xcd blocks of 1 tile", dict(xcd_block_tiles=1)), ("xcd blocks of 8", dict(xcd_block_tiles=8)),
-                ("xcd blocks of 64", dict(xcd_block_tiles=64)), ("xcd blocks of 512", dict(xcd_block_tiles=512)),
-                ("xcd blocks of 4096", dict(xcd_block_tiles=4096)),
-                ("order 1", dict(order=1)), ("order 2", dict(order=2)), ("order 3", dict(order=3)),
-                ("128 lanes", dict(threads=128)), ("512 lanes", dict(threads=512)), ("1024 lanes", dict(threads=1024)),
-                ("unroll 2", dict(unroll=2)), ("unroll 4", dict(unroll=4)), ("512 lanes, unroll 2", dict(threads=512, unroll=2)),
-                ("default cache policy", dict(nontemporal=1)), ("non-temporal", dict(nontemporal=2)),
-                ("non-temporal loads, agent-scope stores", dict(nontemporal=3)),
-                ("2 workgroups per CU", dict(workgroups_per_cu=2)), ("4 workgroups per CU", dict(workgroups_per_cu=4)),
-                ("6 workgroups per CU", dict(workgroups_per_cu=6)),
-                ("defaults again", {})]
-
-    def rate(ms):
-        return round(2 * s.payload / ms / 1e6, 1)
-    for name, cfg in settings:
-        kvx.kvx_plan_set_launch(p, **cfg)
-        tp = s.time_op(lambda: s.pack(p), iters=6, warmup=1)
-        tu = s.time_op(lambda: s.unpack(p), iters=6, warmup=1)
-        tc = s.time_op(lambda: s.convert(p), iters=6, warmup=1)
-        print(json.dumps({"study": "knobs", "workload": args.workload, "setting": name, "pack_hbm_GBps": rate(tp),
-                          "unpack_hbm_GBps": rate(tu), "convert_hbm_GBps": rate(tc)}), flush=True)
-    p.destroy()
-
-
-def study_placement(args):
-    import torch
-    s = bench.Setup(args.workload, fill=False)
-    kvx = s.kvx
-    p = s.plan()
-
-    def rate(ms):
-        return round(2 * s.payload / ms / 1e6, 1)
-    free, _ = torch.cuda.mem_get_info()
-    count = max(1, min(args.pools, int(0.9 * free) // s.dst.numel()))   # what fits beside the workload itself
-    for rnd in range(3):
-        pools = [torch.empty_like(s.dst) for _ in range(count)]
-        rows = []
-        for d in pools:
-            unpack_ms = s.time_op(lambda: kvx.kvx_unpack(p, s.buf.data_ptr(), s.payload, d.data_ptr(),
-                                                         s.stream.cuda_stream), iters=6, warmup=1)
-            pack_ms = s.time_op(lambda: kvx.kvx_pack(p, d.data_ptr(), s.buf.data_ptr(), s.payload,
-                                                     s.stream.cuda_stream), iters=6, warmup=1)
-            rows.append({"address_MiB": d.data_ptr() >> 20, "unpack_into_hbm_GBps": rate(unpack_ms),
-                         "pack_from_hbm_GBps": rate(pack_ms)})
-        print(json.dumps({"study": "placement", "workload": args.workload, "round": rnd, "pools": rows}), flush=True)
-        del pools, d
-        torch.cuda.empty_cache()
-    p.destroy()
-
-
 def study_slice(args):
     """A head slice of a wider sender pool (sender with all 8 KV heads, receiver holding heads [2,6)):
     the sender is described by explicit strides and a moved base pointer; rows are 1 KiB pieces at a
@@ -406,19 +285,16 @@ def study_slice(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval", "slice", "overlap", "ceilings", "placement", "knobs"])
+    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval", "slice", "overlap"])
     ap.add_argument("--requests", type=int, default=512, help="retrieval: requests of the workload-5 shape")
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 5])
     ap.add_argument("--layers", type=int, default=8, help="blocks: layers of the workload-2 shape to move")
-    ap.add_argument("--gib", type=int, default=4, help="ceilings: GiB copied per launch")
-    ap.add_argument("--pools", type=int, default=8, help="placement: fresh pool allocations per round")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench_studies.py: no GPU visible")
     {"blocks": study_blocks, "layers": study_layers, "layouts": study_layouts,
-     "retrieval": study_retrieval, "slice": study_slice, "overlap": study_overlap,
-     "ceilings": study_ceilings, "placement": study_placement, "knobs": study_knobs}[args.study](args)
+     "retrieval": study_retrieval, "slice": study_slice, "overlap": study_overlap}[args.study](args)
 
 
 if __name__ == "__main__":

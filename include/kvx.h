@@ -15,8 +15,12 @@
  *     memory of the current HIP device.  `stream` is a hipStream_t passed as
  *     void* (NULL = the null stream).
  *   - The caller owns all device memory: pools, buffer and the plan workspace.
- *     The library owns only the host-side plan object.  Host arrays handed to
- *     kvx_plan are copied before it returns.
+ *     The library owns the host-side plan objects and, for batches whose tables
+ *     do not fit a kernel's launch arguments, a few pinned host blocks that
+ *     kvx_plan stages those tables in: they are created on first need
+ *     (hipHostMalloc and an event), handed from plan to plan, kept at a count of
+ *     at most 8 idle ones, and freed by kvx_release_cached.  Host arrays handed
+ *     to kvx_plan are copied before it returns.
  *   - pack / unpack / convert enqueue work on `stream` and return; they never
  *     synchronise and never allocate device memory.  Each is one kernel launch
  *     and nothing else, so these calls (and their _layers forms) may be recorded
@@ -25,8 +29,11 @@
  *     kvx_plan itself may copy from a staging block that the library reuses
  *     and record an event, and must not be called on a capturing stream.
  *   - Every call returns a kvx_status; nothing aborts or throws.  All argument,
- *     geometry and block-table checks happen on the host inside kvx_plan, and a
- *     plan that fails leaves the workspace untouched.
+ *     geometry and block-table checks happen on the host inside kvx_plan, before
+ *     anything is enqueued: a plan refused by one of them leaves the workspace
+ *     untouched.  Only KVX_ERR_DEVICE (a copy or launch that the runtime itself
+ *     rejects) can come after part of the plan's device work was enqueued; the
+ *     workspace contents are then undefined.
  *   - Results are bit-exact copies and do not depend on the launch configuration.
  *
  * Memory model (where the paper is silent, these are this library's readings)
@@ -168,7 +175,8 @@ typedef struct {
                                                   included); 0 if the op is not planned */
 } kvx_plan_tables;
 
-/* Bytes of device workspace kvx_plan needs for these inputs.  `s`/`sb` describe
+/* No passage of the paper: sizing utility.
+ * Bytes of device workspace kvx_plan needs for these inputs.  `s`/`sb` describe
  * the sender side, `d`/`db` the receiver side; either pair may be NULL (then
  * only pack, or only unpack, can be planned).  Checks geometry and that the
  * block tables cover the lengths; the remaining checks are kvx_plan's. */
@@ -196,7 +204,12 @@ kvx_status kvx_plan_workspace_bytes(const kvx_pool_desc *s, const kvx_batch_desc
  *
  * dev_workspace [device] must be 256-byte aligned and at least
  * kvx_plan_workspace_bytes large; it must stay alive and unmodified while the
- * plan is in use.  dev_workspace == NULL with workspace_bytes == 0 builds a
+ * plan is in use.  A receiver given by explicit strides must not let two rows
+ * share bytes: its four axes (token, page, K|V, layer) have to nest, each stride
+ * at least the extent of what lies inside it (stride_token >= row,
+ * stride_page >= (page_tokens-1)*stride_token + row when it is the next larger,
+ * and so on in order of size), else KVX_ERR_INVALID_ARG.  A sender may overlap
+ * itself (it is only read).  dev_workspace == NULL with workspace_bytes == 0 builds a
  * host-only plan: no HIP call is made; totals and segments can be queried but
  * pack / unpack / convert return KVX_ERR_INVALID_ARG.
  *
@@ -207,7 +220,15 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb,
                     void *dev_workspace, size_t workspace_bytes, void *stream,
                     kvx_plan_t **out_plan);
 
+/* No passage of the paper: utility.  Frees the host-side plan object; work already enqueued with the
+ * plan keeps running (launches carry their arguments, and a staging block is reused only after the copy
+ * that reads it has completed).  NULL is a no-op. */
 void kvx_plan_destroy(kvx_plan_t *plan);
+
+/* No passage of the paper: utility.  Frees the pinned staging blocks that destroyed plans left with the
+ * library and whose copies have completed (blocks still being read stay).  `freed_bytes` (may be NULL)
+ * receives the host bytes given back.  Never needed for correctness. */
+kvx_status kvx_release_cached(uint64_t *freed_bytes);
 
 /* Size of the contiguous buffer: (l1-l0) * 2 * num_kv_heads * head_dim *
  * elem_bytes * sum(seq_lens), the KV size formula of section 2.1. */
@@ -223,24 +244,38 @@ kvx_status kvx_plan_segment(const kvx_plan_t *plan, uint32_t request, uint32_t l
 kvx_status kvx_plan_request_segment(const kvx_plan_t *plan, uint32_t request,
                                     uint64_t *offset, uint64_t *length);
 
+/* No passage of the paper: inspection and tuning.  get_tables needs a plan with a device workspace;
+ * set_launch refuses values outside the ranges kvx_launch_cfg states (KVX_ERR_INVALID_ARG). */
 kvx_status kvx_plan_get_tables(const kvx_plan_t *plan, kvx_plan_tables *out);
 kvx_status kvx_plan_set_launch(kvx_plan_t *plan, const kvx_launch_cfg *cfg);
 kvx_status kvx_plan_get_launch(const kvx_plan_t *plan, kvx_launch_cfg *out);
 
-/* Sender: src_pool [device] -> buf [device].  Writes exactly the first
- * kvx_plan_total_bytes bytes of buf; buf_bytes smaller than that is
- * KVX_ERR_CAPACITY.  One kernel launch. */
+/* Section 3.6, "Contiguous Buffer at Sender" (the first of the two converts that section 2.2.3,
+ * "Challenge", says block-free transfer has to pay): the K and V rows of every layer of every request
+ * of the plan, gathered out of the sender's discrete blocks and laid one after another.
+ * src_pool [device] -> buf [device].  Writes exactly the first kvx_plan_total_bytes bytes of buf;
+ * buf_bytes smaller than that is KVX_ERR_CAPACITY.  Needs a plan built with a sender side and a
+ * device workspace (else KVX_ERR_INVALID_ARG); pointers must be 16-byte aligned (KVX_ERR_ALIGNMENT).
+ * One kernel launch on `stream`; neither pointer is kept. */
 kvx_status kvx_pack(const kvx_plan_t *plan, const void *src_pool, void *buf, uint64_t buf_bytes,
                     void *stream);
 
-/* Receiver (RecvScatter): buf [device] -> dst_pool [device].  Writes only the
- * live slots of the pages the receiver's block tables list.  One kernel launch. */
+/* Section 3.6, "RecvScatter at Receiver" (the second convert of section 2.2.3, "Challenge"): the
+ * receiver's discrete blocks restored from the received bytes.  buf [device] -> dst_pool [device].
+ * Reads the first kvx_plan_total_bytes bytes of buf (buf_bytes smaller: KVX_ERR_CAPACITY) and writes
+ * only the live slots of the pages the receiver's block tables list.  Needs a plan built with a
+ * receiver side and a device workspace.  One kernel launch on `stream`. */
 kvx_status kvx_unpack(const kvx_plan_t *plan, const void *buf, uint64_t buf_bytes, void *dst_pool,
                       void *stream);
 
-/* Pool to pool in one launch, equal to kvx_unpack after kvx_pack byte for byte,
- * with independent page sizes and layouts on the two sides.  The pools must not
- * overlap. */
+/* Section 2.2.3, "Opportunity": the bytes in flight carry no block structure, so the block geometry of
+ * the two sides is independent; with both pools on one device the two converts fuse.
+ * src_pool [device] -> dst_pool [device] in one launch, equal to kvx_unpack after kvx_pack byte for
+ * byte, with independent page sizes, layouts and page arrangements on the two sides.  Needs a plan
+ * built with both sides.  The pools must not share bytes: two pools with derived (all-zero) strides
+ * whose extents overlap are refused with KVX_ERR_INVALID_ARG; for a pool given by explicit strides the
+ * library does not know which bytes between its rows belong to it, does not check, and the result of
+ * a convert between aliasing pools is undefined. */
 kvx_status kvx_convert(const kvx_plan_t *plan, const void *src_pool, void *dst_pool, void *stream);
 
 /* Per-layer triggers (section 3.6: either the transfer per layer or of the
@@ -333,26 +368,11 @@ kvx_status kvx_retriever_drain(kvx_retriever_t *ret);
 kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const kvx_launch_cfg *cfg,
                               void *stream);
 
-/* Second yardstick: the same copy cut into chunks that two optional permutations scatter,
- * dst chunk dst_perm[i] <- src chunk src_perm[i] (uint32 tables [device] of bytes/chunk_bytes entries;
- * NULL = identity).  chunk_bytes is a power of two from 4096 up and divides `bytes` (at most 32 GiB);
- * dst and src [device] are 16-byte aligned and do not overlap.  One table lookup per 4 KiB tile and
- * nothing else: what a copy between scattered chunks of a given size can reach on this device, whatever
- * plans it.  The tables live on the device and are NOT checked: every entry must be below
- * bytes/chunk_bytes, and dst_perm must not repeat an entry.
- * Errors: KVX_ERR_INVALID_ARG (NULL buffer, chunk size), KVX_ERR_ALIGNMENT, KVX_ERR_UNSUPPORTED (too large),
- * KVX_ERR_DEVICE. */
-kvx_status kvx_copy_yardstick_chunks(void *dst, const void *src, uint64_t bytes, uint32_t chunk_bytes,
-                                     const uint32_t *src_perm, const uint32_t *dst_perm, void *stream);
+/* No passage of the paper: utility.  A string naming the sources this library was built from (a hash
+ * of them, fixed at build time), so that a loader can tell a stale binary from a current one. */
+const char *kvx_build_id(void);
 
-/* One-way yardsticks: read `bytes` (a multiple of 4096, at most 32 GiB) of buf [device, 16-byte aligned] and
- * write nothing, or fill them with `word` and read nothing, in the data mover's default launch shape.  What the
- * device's memory gives in one direction bounds what any copy can reach.  `sink` [device, 4 bytes] exists
- * only so that the loads have a use; it is written if a 16-byte unit of the data matches one fixed pattern.
- * Errors: KVX_ERR_INVALID_ARG, KVX_ERR_ALIGNMENT, KVX_ERR_UNSUPPORTED (too large), KVX_ERR_DEVICE. */
-kvx_status kvx_read_yardstick(const void *buf, uint64_t bytes, void *sink, void *stream);
-kvx_status kvx_write_yardstick(void *buf, uint64_t bytes, uint32_t word, void *stream);
-
+/* No passage of the paper: utility.  Static text for a status value. */
 const char *kvx_status_string(kvx_status st);
 
 /* The hipError_t value behind this thread's most recent KVX_ERR_DEVICE (0 if none) and, through `where`

@@ -1,4 +1,5 @@
 """Builds libkvx.so (HIP, gfx950) in-tree with hipcc."""
+import hashlib
 import os
 import subprocess
 
@@ -8,14 +9,35 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvx.so")
 SOURCES = [os.path.join(CSRC, "kvx_api.cpp"), os.path.join(CSRC, "kvx_retriever.cpp"),
            os.path.join(CSRC, "kvx_kernels.hip")]
+ID_TAG = "kvx-sources:"
 HEADERS = [os.path.join(CSRC, "kvx_internal.h"), os.path.join(ROOT, "include", "kvx.h")]
 
 
-def is_stale() -> bool:
+def source_id() -> str:
+    """Hash of every file the library is built from; the build bakes it in (kvx_build_id)."""
+    h = hashlib.sha256()
+    for f in SOURCES + HEADERS:
+        h.update(os.path.basename(f).encode() + b"\0")
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:32]
+
+
+def built_id():
+    """The id baked into the built library, read without loading it into this process; None if there is
+    no library or it carries no id."""
     if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
+        return None
+    with open(LIB, "rb") as fh:
+        blob = fh.read()
+    at = blob.find(ID_TAG.encode())
+    if at < 0:
+        return None
+    return blob[at + len(ID_TAG):at + len(ID_TAG) + 32].decode("ascii", "replace")
+
+
+def is_stale() -> bool:
+    return built_id() != source_id()
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
@@ -25,6 +47,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wall", "-Wno-unused-command-line-argument",
+           "-DKVX_BUILD_ID=\"%s%s\"" % (ID_TAG, source_id()),
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            "-x", "hip", *SOURCES, "-o", LIB]
     if verbose:

@@ -25,37 +25,21 @@ void kvx::note_device_error(hipError_t e, const char *where) {
 
 namespace {
 
-constexpr uint64_t kAlign = 256;
-inline uint64_t align_up(uint64_t x, uint64_t a = kAlign) { return (x + a - 1) / a * a; }
-
-struct Geometry {
-    bool present = false;
-    kvx_pool_desc desc{};
-    uint64_t row = 0;
-    uint64_t sl = 0, sk = 0, sp = 0, st = 0; // resolved byte strides
-    bool custom_strides = false;
-    bool dense_rows = true;                  // [token][head][dim] with rows back to back
-    uint32_t quantum = 0;                    // tokens that form one affine span inside a page
-    // 16-byte unit u of the token in slot s sits at s*token_step + (u/upg)*granule_step + (u%upg)*16
-    uint64_t token_step = 0, granule_step = 0;
-    uint32_t upg = 0;
-    bool token_fast = false;                 // consecutive tokens are nearer than consecutive units
-    uint64_t used_pages = 0;                 // sum over requests of ceil(n/P)
-};
-
 // Pinned staging blocks are costly to create, so destroyed plans hand theirs
 // back to a small free list instead of freeing them.  A block carries an event
-// recorded behind the H2D copy that reads it; it is handed out again only once
-// that event has completed, so a plan destroyed with work still queued never
-// has its staged tables overwritten before they were copied.
-struct PinnedBlock {
-    void *ptr = nullptr;
-    size_t bytes = 0;
-    hipEvent_t copied = nullptr;
-    int device = -1; // the event belongs to this device: a block serves plans of that device only
-};
+// recorded behind the H2D copy that reads it; it is handed out again, or freed,
+// only once that event has completed, so a plan destroyed with work still
+// queued never has its staged tables overwritten or unmapped before they were
+// copied.  The list keeps at most kPinnedKeep blocks whose copies are done;
+// kvx_release_cached frees those on request.
+constexpr size_t kPinnedKeep = 8;
 std::mutex g_pinned_mu;
 std::vector<PinnedBlock> g_pinned_free;
+
+void pinned_free_block(const PinnedBlock &b) {
+    (void)hipHostFree(b.ptr);
+    (void)hipEventDestroy(b.copied);
+}
 
 hipError_t pinned_acquire(size_t bytes, PinnedBlock *out) {
     int device = 0;
@@ -90,14 +74,57 @@ hipError_t pinned_acquire(size_t bytes, PinnedBlock *out) {
     return hipSuccess;
 }
 
+// Frees listed blocks whose copies have completed, oldest first, until at most `keep` such blocks are left.
+// Blocks still being read stay listed whatever `keep` says.  Returns the bytes freed.  Caller holds the lock.
+uint64_t pinned_trim(size_t keep) {
+    size_t done = 0;
+    for (const PinnedBlock &b : g_pinned_free)
+        if (hipEventQuery(b.copied) == hipSuccess) ++done;
+    uint64_t freed = 0;
+    size_t w = 0;
+    for (size_t i = 0; i < g_pinned_free.size(); ++i) {
+        // a block that completed between the two queries is only kept a little longer
+        if (done > keep && hipEventQuery(g_pinned_free[i].copied) == hipSuccess) {
+            freed += g_pinned_free[i].bytes;
+            pinned_free_block(g_pinned_free[i]);
+            --done;
+        } else {
+            g_pinned_free[w++] = g_pinned_free[i];
+        }
+    }
+    g_pinned_free.resize(w);
+    return freed;
+}
+
 void pinned_release(PinnedBlock b) {
     if (!b.ptr) return;
     std::lock_guard<std::mutex> lk(g_pinned_mu);
-    // Never unmapped while a copy may still read it: the list simply grows.
     g_pinned_free.push_back(b);
+    if (g_pinned_free.size() > kPinnedKeep) (void)pinned_trim(kPinnedKeep);
 }
 
-kvx_status resolve_pool(const kvx_pool_desc *d, Geometry *g) {
+} // namespace
+
+namespace kvx {
+
+// Explicit strides of a pool that is written: the four axes (token, page, K|V, layer) must nest, every
+// stride at least the extent of everything that lies inside it, so that no two rows share a byte.  An axis
+// of extent 1 has no say.
+static bool strides_nest(const kvx_pool_desc *d, uint64_t row) {
+    struct Axis { uint64_t stride, extent; };
+    Axis ax[4] = {{d->stride_token, d->page_tokens}, {d->stride_page, d->num_pages}, {d->stride_kv, 2},
+                  {d->stride_layer, d->num_layers}};
+    std::sort(ax, ax + 4, [](const Axis &a, const Axis &b) { return a.stride < b.stride; });
+    unsigned __int128 inner = row; // bytes covered by everything inside the axis being looked at
+    for (const Axis &a : ax) {
+        if (a.extent == 1) continue;
+        if ((unsigned __int128)a.stride < inner) return false;
+        inner = (unsigned __int128)a.stride * (a.extent - 1) + inner;
+    }
+    return true;
+}
+
+kvx_status resolve_pool(const kvx_pool_desc *d, bool receiver, Geometry *g) {
     if (!d->num_layers || !d->num_kv_heads || !d->head_dim || !d->elem_bytes || !d->page_tokens ||
         !d->num_pages || d->inner > KVX_INNER_DIM_SPLIT_TOKEN)
         return KVX_ERR_INVALID_ARG;
@@ -120,6 +147,7 @@ kvx_status resolve_pool(const kvx_pool_desc *d, Geometry *g) {
         if ((d->stride_layer | d->stride_kv | d->stride_page | d->stride_token) % 16)
             return KVX_ERR_ALIGNMENT;
         if (d->stride_token < row) return KVX_ERR_INVALID_ARG;
+        if (receiver && !strides_nest(d, row)) return KVX_ERR_INVALID_ARG;
         g->custom_strides = true;
         g->sl = d->stride_layer;
         g->sk = d->stride_kv;
@@ -156,6 +184,15 @@ kvx_status resolve_pool(const kvx_pool_desc *d, Geometry *g) {
         g->granule_step = 16ull * d->page_tokens;
         g->token_fast = true;
     }
+    // last byte of the last row, one past: pages of every arrangement hold page_tokens * row bytes
+    {
+        const unsigned __int128 span = (unsigned __int128)(d->num_layers - 1) * g->sl + g->sk +
+                                       (unsigned __int128)(d->num_pages - 1) * g->sp +
+                                       (g->custom_strides ? (unsigned __int128)(d->page_tokens - 1) * g->st + row
+                                                          : (unsigned __int128)d->page_tokens * row);
+        if (span >> 63) return KVX_ERR_UNSUPPORTED;
+        g->span = (uint64_t)span;
+    }
     return KVX_OK;
 }
 
@@ -169,6 +206,10 @@ kvx_status check_batch_shape(const kvx_batch_desc *b) {
     if (b->block_offsets[b->num_requests] && !b->block_ids) return KVX_ERR_INVALID_ARG;
     return KVX_OK;
 }
+
+} // namespace kvx
+
+namespace {
 
 // Checks one side's block tables against its pool and gathers the ids that
 // are actually used (the first ceil(n/P) of each request) into `compact`.
@@ -213,28 +254,10 @@ uint64_t lcm_q(uint32_t a, uint32_t b) {
     return (uint64_t)a / std::gcd(a, b) * b;
 }
 
-struct OpShape {
-    bool planned = false;
-    uint32_t qa = 0, qb = 0;
-    uint64_t lcm = 0;
-    uint64_t num_runs = 0;       // records in the device table (for convert: slots, some empty)
-    uint32_t max_run_bytes = 0;
-    uint32_t group_quantum = 0;  // convert: tokens per group = the coarser side's quantum
-    uint32_t group_slots = 1;    // convert: slots per group
-};
+} // namespace
 
-// Sizes shared by kvx_plan_workspace_bytes and kvx_plan.
-struct Sizing {
-    uint32_t R = 0;
-    OpShape ops[NUM_OPS];
-    uint64_t off_lens = 0, off_ids_s = 0, off_ids_d = 0, staging_bytes = 0;
-    uint64_t off_prefix[kNumScans] = {};
-    uint64_t off_runs[NUM_OPS] = {};
-    uint64_t total_bytes = 0;
-};
-
-void shape_ops(const Geometry &s, const Geometry &d, const uint32_t *seq_lens, uint32_t R,
-               OpShape ops[NUM_OPS]) {
+void kvx::shape_ops(const Geometry &s, const Geometry &d, const uint32_t *seq_lens, uint32_t R,
+                    OpShape ops[NUM_OPS]) {
     if (s.present) {
         ops[OP_PACK].planned = true;
         ops[OP_PACK].qa = s.quantum;
@@ -275,7 +298,7 @@ void shape_ops(const Geometry &s, const Geometry &d, const uint32_t *seq_lens, u
     }
 }
 
-void layout_workspace(Sizing *z, uint64_t used_s, uint64_t used_d) {
+void kvx::layout_workspace(Sizing *z, uint64_t used_s, uint64_t used_d) {
     uint64_t off = 0;
     z->off_lens = off;
     off = align_up(off + 4ull * z->R);
@@ -295,16 +318,18 @@ void layout_workspace(Sizing *z, uint64_t used_s, uint64_t used_d) {
     z->total_bytes = std::max<uint64_t>(off, kAlign);
 }
 
+namespace {
+
 kvx_status check_sides(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_pool_desc *d,
                        const kvx_batch_desc *db, Geometry *gs, Geometry *gd) {
     if ((!s) != (!sb) || (!d) != (!db) || (!s && !d)) return KVX_ERR_INVALID_ARG;
     kvx_status st;
     if (s) {
-        if ((st = resolve_pool(s, gs)) != KVX_OK) return st;
+        if ((st = resolve_pool(s, false, gs)) != KVX_OK) return st;
         if ((st = check_batch_shape(sb)) != KVX_OK) return st;
     }
     if (d) {
-        if ((st = resolve_pool(d, gd)) != KVX_OK) return st;
+        if ((st = resolve_pool(d, true, gd)) != KVX_OK) return st;
         if ((st = check_batch_shape(db)) != KVX_OK) return st;
     }
     if (s && d) {
@@ -320,29 +345,14 @@ kvx_status check_sides(const kvx_pool_desc *s, const kvx_batch_desc *sb, const k
 
 } // namespace
 
-struct kvx_plan_s {
-    Geometry s, d;
-    uint32_t R = 0;
-    uint32_t l0 = 0, l1 = 0;
-    uint64_t row = 0;
-    uint64_t bpt = 0;
-    uint64_t total = 0;
-    std::vector<uint32_t> seq_lens;
-    std::vector<uint64_t> token_prefix; // T_r, host copy for segment queries
-    std::vector<uint32_t> ids_s;        // sender's used page ids, request by request (for the block-by-block baseline)
-    Sizing z;
-    char *ws = nullptr; // device workspace (caller's), nullptr for a host-only plan
-    PinnedBlock staging;
-    kvx_launch_cfg launch{};
-};
-
-namespace {
 // Fields the library fills at once; order, threads, unroll and nontemporal stay 0 (= chosen per operation
 // at launch).
-void default_launch(kvx_launch_cfg *c) {
+void kvx::default_launch(kvx_launch_cfg *c) {
     if (!c->xcd_swizzle) c->xcd_swizzle = 2;
     if (!c->max_workgroups) c->max_workgroups = 1u << 24;
 }
+
+namespace {
 
 // Tile shape when the caller left it open.  Measured on MI355X: with (layer,kv) outermost the smallest
 // tile (256 lanes x 16 B) with the largest grid is fastest; with the run group outermost (page-major
@@ -367,6 +377,58 @@ void resolve_tile(uint32_t order, uint32_t max_run_bytes, uint32_t *threads, uin
     if (!*unroll) *unroll = u;
 }
 } // namespace
+
+void kvx::planner_params(const kvx_plan_s &p, ScanParams *scan, FillParams *fill) {
+    const Sizing &z = p.z;
+    ScanParams sp{};
+    FillParams fp{};
+    sp.seq_lens = reinterpret_cast<const uint32_t *>(p.ws + z.off_lens);
+    sp.num_requests = p.R;
+    sp.page_s = p.s.present ? p.s.desc.page_tokens : 0;
+    sp.page_d = p.d.present ? p.d.desc.page_tokens : 0;
+    fp.seq_lens = sp.seq_lens;
+    fp.token_prefix = reinterpret_cast<const uint64_t *>(p.ws + z.off_prefix[SCAN_TOKENS]);
+    fp.num_requests = p.R;
+    fp.row = (uint32_t)p.row;
+    fp.bytes_per_token = p.bpt;
+    for (int k = 0; k < kNumScans; ++k) sp.prefix[k] = reinterpret_cast<uint64_t *>(p.ws + z.off_prefix[k]);
+    SideGeom src_side{}, dst_side{}, buf_side{};
+    if (p.s.present) {
+        src_side.ids = reinterpret_cast<const uint32_t *>(p.ws + z.off_ids_s);
+        src_side.page_prefix = sp.prefix[SCAN_PAGES_S];
+        src_side.stride_page = p.s.sp;
+        src_side.stride_token = p.s.token_step;
+        src_side.page_tokens = p.s.desc.page_tokens;
+        src_side.quantum = p.s.quantum;
+    }
+    if (p.d.present) {
+        dst_side.ids = reinterpret_cast<const uint32_t *>(p.ws + z.off_ids_d);
+        dst_side.page_prefix = sp.prefix[SCAN_PAGES_D];
+        dst_side.stride_page = p.d.sp;
+        dst_side.stride_token = p.d.token_step;
+        dst_side.page_tokens = p.d.desc.page_tokens;
+        dst_side.quantum = p.d.quantum;
+    }
+    fp.src[OP_PACK] = src_side;   fp.dst[OP_PACK] = buf_side;
+    fp.src[OP_UNPACK] = buf_side; fp.dst[OP_UNPACK] = dst_side;
+    fp.src[OP_CONVERT] = src_side; fp.dst[OP_CONVERT] = dst_side;
+    for (int op = 0; op < (int)NUM_OPS; ++op) {
+        sp.qa[op] = z.ops[op].qa;
+        sp.qb[op] = z.ops[op].qb;
+        sp.lcm[op] = z.ops[op].lcm;
+        sp.planned[op] = z.ops[op].planned;
+        fp.lcm[op] = z.ops[op].lcm;
+        fp.planned[op] = z.ops[op].planned;
+        if (op == OP_CONVERT) {
+            sp.group_quantum = fp.group_quantum = z.ops[op].group_quantum;
+            sp.group_slots = fp.group_slots = z.ops[op].group_slots;
+        }
+        fp.run_prefix[op] = sp.prefix[SCAN_RUNS0 + op];
+        fp.runs[op] = reinterpret_cast<kvx_run *>(p.ws + z.off_runs[op]);
+    }
+    *scan = sp;
+    *fill = fp;
+}
 
 extern "C" {
 
@@ -482,51 +544,8 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
         }
 
         ScanParams sp{};
-        sp.seq_lens = reinterpret_cast<const uint32_t *>(p->ws + z.off_lens);
-        sp.num_requests = R;
-        sp.page_s = s ? s->page_tokens : 0;
-        sp.page_d = d ? d->page_tokens : 0;
         FillParams fp{};
-        fp.seq_lens = sp.seq_lens;
-        fp.token_prefix = reinterpret_cast<const uint64_t *>(p->ws + z.off_prefix[SCAN_TOKENS]);
-        fp.num_requests = R;
-        fp.row = (uint32_t)p->row;
-        fp.bytes_per_token = p->bpt;
-        for (int k = 0; k < kNumScans; ++k) sp.prefix[k] = reinterpret_cast<uint64_t *>(p->ws + z.off_prefix[k]);
-        SideGeom src_side{}, dst_side{}, buf_side{};
-        if (s) {
-            src_side.ids = reinterpret_cast<const uint32_t *>(p->ws + z.off_ids_s);
-            src_side.page_prefix = sp.prefix[SCAN_PAGES_S];
-            src_side.stride_page = p->s.sp;
-            src_side.stride_token = p->s.token_step;
-            src_side.page_tokens = s->page_tokens;
-            src_side.quantum = p->s.quantum;
-        }
-        if (d) {
-            dst_side.ids = reinterpret_cast<const uint32_t *>(p->ws + z.off_ids_d);
-            dst_side.page_prefix = sp.prefix[SCAN_PAGES_D];
-            dst_side.stride_page = p->d.sp;
-            dst_side.stride_token = p->d.token_step;
-            dst_side.page_tokens = d->page_tokens;
-            dst_side.quantum = p->d.quantum;
-        }
-        fp.src[OP_PACK] = src_side;   fp.dst[OP_PACK] = buf_side;
-        fp.src[OP_UNPACK] = buf_side; fp.dst[OP_UNPACK] = dst_side;
-        fp.src[OP_CONVERT] = src_side; fp.dst[OP_CONVERT] = dst_side;
-        for (int op = 0; op < (int)NUM_OPS; ++op) {
-            sp.qa[op] = z.ops[op].qa;
-            sp.qb[op] = z.ops[op].qb;
-            sp.lcm[op] = z.ops[op].lcm;
-            sp.planned[op] = z.ops[op].planned;
-            fp.lcm[op] = z.ops[op].lcm;
-            fp.planned[op] = z.ops[op].planned;
-            if (op == OP_CONVERT) {
-                sp.group_quantum = fp.group_quantum = z.ops[op].group_quantum;
-                sp.group_slots = fp.group_slots = z.ops[op].group_slots;
-            }
-            fp.run_prefix[op] = sp.prefix[SCAN_RUNS0 + op];
-            fp.runs[op] = reinterpret_cast<kvx_run *>(p->ws + z.off_runs[op]);
-        }
+        planner_params(*p, &sp, &fp);
         if (tables_inline)
             ok = ok && hip_ok(launch_scan_inline(sp, it, reinterpret_cast<uint32_t *>(p->ws), hs),
                               "scan_inline_kernel launch");
@@ -543,6 +562,18 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
 } catch (...) { // the host tables could not be allocated; nothing was enqueued yet
     return KVX_ERR_HOST_MEMORY;
 }
+
+kvx_status kvx_release_cached(uint64_t *freed_bytes) {
+    std::lock_guard<std::mutex> lk(g_pinned_mu);
+    const uint64_t freed = pinned_trim(0);
+    if (freed_bytes) *freed_bytes = freed;
+    return KVX_OK;
+}
+
+#ifndef KVX_BUILD_ID
+#define KVX_BUILD_ID "unknown"
+#endif
+const char *kvx_build_id(void) { return KVX_BUILD_ID; }
 
 void kvx_plan_destroy(kvx_plan_t *plan) {
     if (!plan) return;
@@ -672,14 +703,21 @@ kvx_status run_xpose(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, co
 
 // Launches one operation over layers [lb, le) of the plan's range.  Buffer offsets stay those of the
 // plan's whole range, so a sub-range touches exactly its own segments of the same buffer.
-kvx_status run_op(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, const void *src, void *dst,
-                  void *stream) {
+} // namespace
+
+kvx_status kvx::run_op(const kvx_plan_s *plan, Op op, uint32_t lb, uint32_t le, const void *src, void *dst,
+                       void *stream) {
     const OpShape &o = plan->z.ops[op];
     if (!plan->ws || !o.planned) return KVX_ERR_INVALID_ARG;
     if (lb > le || lb < plan->l0 || le > plan->l1) return KVX_ERR_INVALID_ARG;
     if (plan->total == 0 || lb == le) return KVX_OK;
     if (!src || !dst) return KVX_ERR_INVALID_ARG;
     if (((uintptr_t)src | (uintptr_t)dst) % 16) return KVX_ERR_ALIGNMENT;
+    if (op == OP_CONVERT && !plan->s.custom_strides && !plan->d.custom_strides) {
+        // two dense pools: their extents are known, so an overlap can be refused
+        const uintptr_t a = (uintptr_t)src, b = (uintptr_t)dst;
+        if (a < b + plan->d.span && b < a + plan->s.span) return KVX_ERR_INVALID_ARG;
+    }
     const kvx_launch_cfg &c = plan->launch;
     const bool src_rows = (op == OP_UNPACK) || plan->s.dense_rows;
     const bool dst_rows = (op == OP_PACK) || plan->d.dense_rows;
@@ -745,8 +783,6 @@ kvx_status run_op(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, const
                                static_cast<hipStream_t>(stream));
     return hip_ok(e, "copy_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
 }
-
-} // namespace
 
 extern "C" {
 
@@ -842,36 +878,6 @@ kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const 
                                      c.unroll, c.nontemporal ? (int)c.nontemporal - 1 : 2, c.max_workgroups,
                                      static_cast<hipStream_t>(stream));
     return hip_ok(e, "plain_copy_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
-}
-
-kvx_status kvx_copy_yardstick_chunks(void *dst, const void *src, uint64_t bytes, uint32_t chunk_bytes,
-                                     const uint32_t *src_perm, const uint32_t *dst_perm, void *stream) {
-    if (!dst || !src || chunk_bytes < 4096 || (chunk_bytes & (chunk_bytes - 1)) || bytes % chunk_bytes)
-        return KVX_ERR_INVALID_ARG;
-    if (((uintptr_t)dst | (uintptr_t)src) % 16) return KVX_ERR_ALIGNMENT;
-    if (bytes / 4096 >= (1ull << 31) / 256) return KVX_ERR_UNSUPPORTED; // one tile per workgroup, no loop
-    uint32_t lg = 0;
-    while ((4096u << lg) < chunk_bytes) ++lg;
-    hipError_t e = launch_chunk_copy(static_cast<char *>(dst), static_cast<const char *>(src), bytes, lg, src_perm,
-                                     dst_perm, static_cast<hipStream_t>(stream));
-    return hip_ok(e, "chunk_copy_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
-}
-
-kvx_status kvx_read_yardstick(const void *buf, uint64_t bytes, void *sink, void *stream) {
-    if (!buf || !sink || bytes % 4096) return KVX_ERR_INVALID_ARG;
-    if ((uintptr_t)buf % 16 || (uintptr_t)sink % 4) return KVX_ERR_ALIGNMENT;
-    if (bytes / 4096 >= (1ull << 31) / 256) return KVX_ERR_UNSUPPORTED;
-    hipError_t e = launch_one_way(const_cast<char *>(static_cast<const char *>(buf)), bytes, false, 0,
-                                  static_cast<uint32_t *>(sink), static_cast<hipStream_t>(stream));
-    return hip_ok(e, "read_only_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
-}
-
-kvx_status kvx_write_yardstick(void *buf, uint64_t bytes, uint32_t word, void *stream) {
-    if (!buf || bytes % 4096) return KVX_ERR_INVALID_ARG;
-    if ((uintptr_t)buf % 16) return KVX_ERR_ALIGNMENT;
-    if (bytes / 4096 >= (1ull << 31) / 256) return KVX_ERR_UNSUPPORTED;
-    hipError_t e = launch_one_way(static_cast<char *>(buf), bytes, true, word, nullptr, static_cast<hipStream_t>(stream));
-    return hip_ok(e, "write_only_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
 }
 
 int kvx_last_device_error(const char **where) {

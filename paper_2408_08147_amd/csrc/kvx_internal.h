@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "kvx.h"
 
 namespace kvx {
@@ -150,9 +152,87 @@ inline uint32_t occupancy_lds(uint32_t per_cu) { return per_cu ? kLdsPerCu / per
 hipError_t launch_plain_copy(char *dst, const char *src, uint64_t bytes, uint32_t threads, uint32_t unroll,
                              int nontemporal, uint32_t max_wg, hipStream_t stream);
 
-hipError_t launch_one_way(char *buf, uint64_t bytes, bool write, uint32_t word, uint32_t *sink, hipStream_t stream);
+// ---------------------------------------------------------------------------
+// Host side: what kvx_plan works out about a pool, an operation and the workspace
+// ---------------------------------------------------------------------------
+constexpr uint64_t kAlign = 256;
+inline uint64_t align_up(uint64_t x, uint64_t a = kAlign) { return (x + a - 1) / a * a; }
 
-hipError_t launch_chunk_copy(char *dst, const char *src, uint64_t bytes, uint32_t log2_tiles_per_chunk,
-                             const uint32_t *src_perm, const uint32_t *dst_perm, hipStream_t stream);
+struct Geometry {
+    bool present = false;
+    kvx_pool_desc desc{};
+    uint64_t row = 0;
+    uint64_t sl = 0, sk = 0, sp = 0, st = 0; // resolved byte strides
+    bool custom_strides = false;
+    bool dense_rows = true;                  // [token][head][dim] with rows back to back
+    uint32_t quantum = 0;                    // tokens that form one affine span inside a page
+    // 16-byte unit u of the token in slot s sits at s*token_step + (u/upg)*granule_step + (u%upg)*16
+    uint64_t token_step = 0, granule_step = 0;
+    uint32_t upg = 0;
+    bool token_fast = false;                 // consecutive tokens are nearer than consecutive units
+    uint64_t span = 0;                       // bytes from the pool's base to the end of its last row
+    uint64_t used_pages = 0;                 // sum over requests of ceil(n/P)
+};
+
+struct OpShape {
+    bool planned = false;
+    uint32_t qa = 0, qb = 0;
+    uint64_t lcm = 0;
+    uint64_t num_runs = 0;       // records in the device table (for convert: slots, some empty)
+    uint32_t max_run_bytes = 0;
+    uint32_t group_quantum = 0;  // convert: tokens per group = the coarser side's quantum
+    uint32_t group_slots = 1;    // convert: slots per group
+};
+
+// Sizes shared by kvx_plan_workspace_bytes and kvx_plan.
+struct Sizing {
+    uint32_t R = 0;
+    OpShape ops[NUM_OPS];
+    uint64_t off_lens = 0, off_ids_s = 0, off_ids_d = 0, staging_bytes = 0;
+    uint64_t off_prefix[kNumScans] = {};
+    uint64_t off_runs[NUM_OPS] = {};
+    uint64_t total_bytes = 0;
+};
+
+// A pinned staging block and the event recorded behind the copy that reads it.
+struct PinnedBlock {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+    hipEvent_t copied = nullptr;
+    int device = -1; // the event belongs to this device: a block serves plans of that device only
+};
+
+// `receiver`: the pool will be written, so its explicit strides must not let two rows share bytes.
+kvx_status resolve_pool(const kvx_pool_desc *d, bool receiver, Geometry *g);
+kvx_status check_batch_shape(const kvx_batch_desc *b);
+void shape_ops(const Geometry &s, const Geometry &d, const uint32_t *seq_lens, uint32_t R, OpShape ops[NUM_OPS]);
+void layout_workspace(Sizing *z, uint64_t used_s, uint64_t used_d);
+void default_launch(kvx_launch_cfg *c);
+
+} // namespace kvx
+
+struct kvx_plan_s {
+    kvx::Geometry s, d;
+    uint32_t R = 0;
+    uint32_t l0 = 0, l1 = 0;
+    uint64_t row = 0;
+    uint64_t bpt = 0;
+    uint64_t total = 0;
+    std::vector<uint32_t> seq_lens;
+    std::vector<uint64_t> token_prefix; // T_r, host copy for segment queries
+    std::vector<uint32_t> ids_s;        // sender's used page ids, request by request (for the block-by-block baseline)
+    kvx::Sizing z;
+    char *ws = nullptr; // device workspace (caller's), nullptr for a host-only plan
+    kvx::PinnedBlock staging;
+    kvx_launch_cfg launch{};
+};
+
+namespace kvx {
+
+// Fills the two planning kernels' parameters from a plan whose geometry, sizes and workspace are set.
+void planner_params(const kvx_plan_s &p, ScanParams *sp, FillParams *fp);
+
+// Launches one operation over layers [lb, le) of the plan's range.
+kvx_status run_op(const kvx_plan_s *plan, Op op, uint32_t lb, uint32_t le, const void *src, void *dst, void *stream);
 
 } // namespace kvx

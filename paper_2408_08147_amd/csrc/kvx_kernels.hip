@@ -335,14 +335,15 @@ __global__ __launch_bounds__(T) void copy_kernel(const kvx_run *__restrict__ run
         const char *sp = src + so + lane_off;
         char *dp = dst + dk + lane_off;
 
-        u32x4 r[U];
         if (rem >= kTile) {
+            u32x4 r[U];
 #pragma unroll
             for (int k = 0; k < U; ++k) r[k] = ld16<NT>(sp + k * kStep);
             loads_done_before_asm_stores<NT>(r);
 #pragma unroll
             for (int k = 0; k < U; ++k) st16<NT>(dp + k * kStep, r[k]);
         } else {
+            u32x4 r[U] = {}; // lanes past the end load nothing, yet every register is handed to the asm below
 #pragma unroll
             for (int k = 0; k < U; ++k)
                 if (lane_off + k * kStep < rem) r[k] = ld16<NT>(sp + k * kStep);
@@ -416,7 +417,7 @@ __global__ __launch_bounds__(kXposeThreads) void xpose_kernel(const kvx_run *__r
         const char *sp = src + run.src_off + (p.s.is_buf ? seg : layer * p.s.stride_layer + kv * p.s.stride_kv);
         char *dp = dst + run.dst_off + (p.d.is_buf ? seg : layer * p.d.stride_layer + kv * p.d.stride_kv);
 
-        u32x4 r[kPerLane];
+        u32x4 r[kPerLane] = {}; // cells outside the run load nothing, yet every register is handed on below
         bool ok[kPerLane];
 #pragma unroll
         for (int k = 0; k < kPerLane; ++k) {
@@ -465,14 +466,15 @@ __global__ __launch_bounds__(T) void plain_copy_kernel(const char *__restrict__ 
         const uint64_t rem = bytes - base;
         const char *sp = src + base + lane_off;
         char *dp = dst + base + lane_off;
-        u32x4 r[U];
         if (rem >= kTile) {
+            u32x4 r[U];
 #pragma unroll
             for (int k = 0; k < U; ++k) r[k] = ld16<NT>(sp + k * kStep);
             loads_done_before_asm_stores<NT>(r);
 #pragma unroll
             for (int k = 0; k < U; ++k) st16<NT>(dp + k * kStep, r[k]);
         } else {
+            u32x4 r[U] = {}; // lanes past the end load nothing, yet every register is handed to the asm below
 #pragma unroll
             for (int k = 0; k < U; ++k)
                 if (lane_off + k * kStep < rem) r[k] = ld16<NT>(sp + k * kStep);
@@ -482,42 +484,6 @@ __global__ __launch_bounds__(T) void plain_copy_kernel(const char *__restrict__ 
                 if (lane_off + k * kStep < rem) st16<NT>(dp + k * kStep, r[k]);
         }
     }
-}
-
-// One-way yardsticks, one 4 KiB tile per workgroup like the data mover's default shape: only loads, or only
-// stores.  The loads feed a value that is stored if it matches a pattern no lane will ever compute, so the
-// compiler has to keep them while nothing is written.
-__global__ __launch_bounds__(256) void read_only_kernel(const char *__restrict__ src, uint32_t *__restrict__ sink,
-                                                        uint32_t total_tiles, uint32_t swizzle_chunk) {
-    const uint32_t b = (blockIdx.x & 7u) * swizzle_chunk + (blockIdx.x >> 3);
-    if (b >= total_tiles) return;
-    const u32x4 v = ld16<1>(src + (uint64_t)b * 4096u + threadIdx.x * 16u);
-    if ((v.x ^ v.y) == 0x9E3779B9u && (v.z ^ v.w) == 0x7F4A7C15u && v.x == 0x2545F491u) *sink = v.w;
-}
-
-__global__ __launch_bounds__(256) void write_only_kernel(char *__restrict__ dst, uint32_t word, uint32_t total_tiles,
-                                                         uint32_t swizzle_chunk) {
-    const uint32_t b = (blockIdx.x & 7u) * swizzle_chunk + (blockIdx.x >> 3);
-    if (b >= total_tiles) return;
-    const u32x4 v = {word, word, word, word};
-    st16<1>(dst + (uint64_t)b * 4096u + threadIdx.x * 16u, v);
-}
-
-// Second yardstick: chunk-permuted copy, one 4 KiB tile per workgroup, the data mover's default shape.
-__global__ __launch_bounds__(256) void chunk_copy_kernel(const uint32_t *__restrict__ src_perm,
-                                                         const uint32_t *__restrict__ dst_perm,
-                                                         const char *__restrict__ src, char *__restrict__ dst,
-                                                         uint32_t log2_tiles_per_chunk, uint32_t total_tiles,
-                                                         uint32_t swizzle_chunk) {
-    const uint32_t b = (blockIdx.x & 7u) * swizzle_chunk + (blockIdx.x >> 3);
-    if (b >= total_tiles) return;
-    const uint32_t chunk = b >> log2_tiles_per_chunk;
-    const uint32_t within = b & ((1u << log2_tiles_per_chunk) - 1u);
-    const uint64_t chunk_bytes = 4096ull << log2_tiles_per_chunk;
-    const uint64_t s_chunk = src_perm ? src_perm[chunk] : chunk;
-    const uint64_t d_chunk = dst_perm ? dst_perm[chunk] : chunk;
-    const uint64_t off = within * 4096ull + threadIdx.x * 16u;
-    st16<1>(dst + d_chunk * chunk_bytes + off, ld16<1>(src + s_chunk * chunk_bytes + off));
 }
 
 // ---------------------------------------------------------------------------
@@ -659,25 +625,6 @@ hipError_t launch_xpose(const XposeParams &p, bool src_token_fast, bool dst_toke
                               : xpose_sd<true, false>(p, nontemporal, grid, stream);
     return dst_token_fast ? xpose_sd<false, true>(p, nontemporal, grid, stream)
                           : xpose_sd<false, false>(p, nontemporal, grid, stream);
-}
-
-hipError_t launch_one_way(char *buf, uint64_t bytes, bool write, uint32_t word, uint32_t *sink, hipStream_t stream) {
-    const uint32_t tiles = (uint32_t)(bytes / 4096);
-    if (tiles == 0) return hipSuccess;
-    const uint32_t grid = (tiles + 7u) / 8u * 8u;
-    if (write) KVX_LAUNCH(write_only_kernel, dim3(grid), dim3(256), 0, stream, buf, word, tiles, grid / 8u);
-    else KVX_LAUNCH(read_only_kernel, dim3(grid), dim3(256), 0, stream, buf, sink, tiles, grid / 8u);
-    return hipGetLastError();
-}
-
-hipError_t launch_chunk_copy(char *dst, const char *src, uint64_t bytes, uint32_t log2_tiles_per_chunk,
-                             const uint32_t *src_perm, const uint32_t *dst_perm, hipStream_t stream) {
-    const uint32_t tiles = (uint32_t)(bytes / 4096);
-    if (tiles == 0) return hipSuccess;
-    const uint32_t grid = (tiles + 7u) / 8u * 8u;
-    KVX_LAUNCH(chunk_copy_kernel, dim3(grid), dim3(256), 0, stream, src_perm, dst_perm, src, dst,
-               log2_tiles_per_chunk, tiles, grid / 8u);
-    return hipGetLastError();
 }
 
 hipError_t launch_plain_copy(char *dst, const char *src, uint64_t bytes, uint32_t threads, uint32_t unroll,

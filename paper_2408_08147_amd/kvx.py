@@ -28,7 +28,7 @@ EXPORTS = (
     "kvx_unpack_layers", "kvx_convert_layers", "kvx_pack_blockwise", "kvx_copy_yardstick",
     "kvx_retriever_arena_bytes", "kvx_retriever_create", "kvx_retriever_destroy", "kvx_retriever_acquire",
     "kvx_retriever_scatter", "kvx_retriever_abandon", "kvx_retriever_poll", "kvx_retriever_drain",
-    "kvx_copy_yardstick_chunks", "kvx_read_yardstick", "kvx_write_yardstick", "kvx_status_string",
+    "kvx_release_cached", "kvx_build_id", "kvx_status_string",
     "kvx_last_device_error",
 )
 
@@ -104,13 +104,16 @@ def lib_path() -> str:
 
 
 def load():
-    """Loads libkvx.so, building it first only when no built library exists."""
+    """Loads libkvx.so.  A library that is missing, or was built from other sources than the ones beside
+    it (the build bakes a hash of them in), is built first; if that cannot be done, loading fails."""
     global _lib
     if _lib is not None:
         return _lib
     path = lib_path()
-    if not os.path.exists(path):
+    if _build.is_stale():
         _build.build()
+        if _build.is_stale():
+            raise RuntimeError(f"{path} does not match the sources in {_build.CSRC} even after a rebuild")
     # The library must share ONE HIP runtime with whoever owns the streams and buffers it is handed.
     # PyTorch wheels carry their own copy of the runtime under another file name: were this library loaded
     # first, the loader would bring in the system copy for it and later PyTorch's for PyTorch, and a stream
@@ -161,13 +164,13 @@ def load():
     lib.kvx_retriever_abandon.argtypes = [C.c_void_p, C.c_uint32]
     lib.kvx_retriever_poll.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.c_uint32, C.POINTER(C.c_uint32)]
     lib.kvx_retriever_drain.argtypes = [C.c_void_p]
-    lib.kvx_copy_yardstick_chunks.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p,
-                                              C.c_void_p, C.c_void_p]
-    lib.kvx_read_yardstick.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
-    lib.kvx_write_yardstick.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p]
     lib.kvx_copy_yardstick.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(LaunchCfg), C.c_void_p]
+    lib.kvx_release_cached.argtypes = [C.POINTER(C.c_uint64)]
+    lib.kvx_build_id.restype = C.c_char_p
+    lib.kvx_build_id.argtypes = []
     for name in EXPORTS:
-        if name not in ("kvx_status_string", "kvx_plan_destroy", "kvx_retriever_destroy", "kvx_last_device_error"):
+        if name not in ("kvx_status_string", "kvx_plan_destroy", "kvx_retriever_destroy", "kvx_last_device_error",
+                        "kvx_build_id"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -386,21 +389,15 @@ def kvx_retriever_drain(ret: Retriever) -> None:
     _check(load().kvx_retriever_drain(ret.handle), "kvx_retriever_drain")
 
 
-def kvx_copy_yardstick_chunks(dst: int, src: int, nbytes: int, chunk_bytes: int, src_perm: int = 0,
-                              dst_perm: int = 0, stream: int = 0) -> None:
-    _check(load().kvx_copy_yardstick_chunks(C.c_void_p(dst or None), C.c_void_p(src or None), nbytes, chunk_bytes,
-                                            C.c_void_p(src_perm or None), C.c_void_p(dst_perm or None),
-                                            C.c_void_p(stream or None)), "kvx_copy_yardstick_chunks")
+def kvx_release_cached() -> int:
+    """Returns the pinned host bytes given back."""
+    out = C.c_uint64(0)
+    _check(load().kvx_release_cached(C.byref(out)), "kvx_release_cached")
+    return out.value
 
 
-def kvx_read_yardstick(buf: int, nbytes: int, sink: int, stream: int = 0) -> None:
-    _check(load().kvx_read_yardstick(C.c_void_p(buf or None), nbytes, C.c_void_p(sink or None),
-                                     C.c_void_p(stream or None)), "kvx_read_yardstick")
-
-
-def kvx_write_yardstick(buf: int, nbytes: int, word: int, stream: int = 0) -> None:
-    _check(load().kvx_write_yardstick(C.c_void_p(buf or None), nbytes, word, C.c_void_p(stream or None)),
-           "kvx_write_yardstick")
+def kvx_build_id() -> str:
+    return load().kvx_build_id().decode()
 
 
 def pool_desc(num_layers: int, num_kv_heads: int, head_dim: int, elem_bytes: int, page_tokens: int,

@@ -44,6 +44,15 @@ int main(int argc, char **argv) {
             s.stride_kv = s.stride_page * s.num_pages;
             s.stride_layer = below(9) == 0 ? 0 : 2 * s.stride_kv;
         }
+        if (below(10) == 0) { // a receiver with explicit strides, nested or (now and then) aliasing
+            const uint64_t row = (uint64_t)d.num_kv_heads * d.head_dim * d.elem_bytes;
+            d.inner = 0;
+            d.stride_token = row + 16 * below(3);
+            d.stride_page = d.stride_token * d.page_tokens + 32 * below(2) - (below(6) == 0 ? 16 : 0);
+            d.stride_kv = d.stride_page * (d.num_pages - (below(6) == 0 ? 1 : 0));
+            d.stride_layer = (below(6) == 0 ? 1 : 2) * d.stride_kv;
+            if (!d.stride_kv) d.stride_kv = d.stride_layer = 16;
+        }
         const uint32_t R = below(7);
         std::vector<uint32_t> lens(R), ids_s, ids_d;
         std::vector<uint64_t> offs_s(R + 1, 0), offs_d(R + 1, 0);

@@ -19,7 +19,7 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 @pytest.mark.gpu
 def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline():
     res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "1", "--steps", "3",
-                          "--warmup", "1"], capture_output=True, text=True, timeout=300)
+                          "--warmup", "1", "--no-other-workloads"], capture_output=True, text=True, timeout=300)
     assert res.returncode == 0, res.stderr[-2000:]
     lines = [l for l in res.stdout.splitlines() if l.strip()]
     assert len(lines) == 1
@@ -35,6 +35,8 @@ def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline():
     cpu = out["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
     assert cpu["gpu_matches_oracle_on_sample"] is True
+    assert cpu["extrapolated_from_layers"] == cpu["of_layers"] == 2      # the tiny workload fits the sample whole
+    assert "other_workloads" not in out
     # value is bytes moved by pack + unpack over the measured step time
     moved = 2 * out["config"]["payload_bytes"] / (out["ms_per_step"] * 1e-3) / 1e9
     assert abs(moved - out["value"]) / moved < 0.01

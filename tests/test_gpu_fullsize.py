@@ -3,7 +3,7 @@ configuration (the one bench.py times).
 
 The pools do not fit the oracle in one piece, so the check is streamed by
 layer: the GPU runs ONE full-range plan (one launch per operation); for each
-sampled layer the sender's slab of that layer is copied to the host, the
+layer the sender's slab of that layer is copied to the host, the
 oracle runs on it as a one-layer pool, and its buffer segments and receiver
 slab (untouched bytes included) are compared byte for byte with what the GPU
 produced for that layer.  Segment positions inside the GPU's full-range buffer
@@ -47,8 +47,8 @@ def run_fullsize(idx, layers_to_check, ops):
     dp = kvx.pool_desc(w.num_layers, w.num_kv_heads, w.head_dim, w.elem_bytes, w.page_d, b.num_pages_d, w.layout_d)
     payload = w.num_layers * 2 * w.row_bytes * b.total_tokens
     need = sp.dense_bytes + dp.dense_bytes + (payload if "pack" in ops else 0)
-    if need > 0.92 * free:
-        pytest.skip(f"needs {need / 2**30:.0f} GiB of device memory, {free / 2**30:.0f} GiB free")
+    # no skip: on an MI355X (288 GB) every workload fits, and a skipped run would leave the workload unchecked
+    assert need <= 0.95 * free, f"needs {need / 2**30:.0f} GiB of device memory, {free / 2**30:.0f} GiB free"
     st = torch.cuda.Stream(device=dev)
     sb = kvx.BatchDesc(b.seq_lens, b.ids_s, b.offs_s)
     db = kvx.BatchDesc(b.seq_lens, b.ids_d, b.offs_d)
@@ -99,6 +99,7 @@ def run_fullsize(idx, layers_to_check, ops):
             bad = np.flatnonzero(got_dst != want_dst)
             raise AssertionError(f"receiver pool differs in layer {layer}: {bad.size} bytes, first {bad[0]}")
         print(f"  layer {layer} ok", flush=True)
+    print(f"workload {idx}: {len(layers_to_check)} of {w.num_layers} layers compared", flush=True)
     plan.destroy()
 
 
@@ -110,12 +111,13 @@ def test_workload_3_full_every_layer():
     run_fullsize(3, list(range(80)), ("pack", "unpack"))
 
 
-def test_workload_5_full_sampled_layers():
-    run_fullsize(5, list(range(0, 40, 2)), ("pack", "unpack"))
+def test_workload_5_full_every_layer():
+    run_fullsize(5, list(range(40)), ("pack", "unpack"))
 
 
-def test_workload_4_full_convert_sampled_layers():
-    run_fullsize(4, [0, 1, 5, 9, 13, 17, 19, 23, 26, 31, 35, 39], ("convert",))
+@pytest.mark.timeout(900)
+def test_workload_4_full_convert_every_layer():
+    run_fullsize(4, list(range(40)), ("convert",))
 
 
 def test_workload_2_full_convert():

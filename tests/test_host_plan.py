@@ -87,6 +87,41 @@ def test_inner_arrangement_errors():
     assert kvx.kvx_plan_total_bytes(p) == 133 * 2 * 2 * 2048
 
 
+def test_receiver_strides_must_not_alias():
+    """A pool that is written must not let two rows share bytes: its four axes have to nest.  A sender is
+    only read and may overlap itself."""
+    _, b = _simple()                              # pages of 16 tokens, rows of 2048 bytes, 64 pages, 2 layers
+    row, P, NP = 2048, 16, 64
+    good = (2 * NP * P * row, NP * P * row, P * row, row)                    # (layer, kv, page, token)
+    padded = (2 * NP * (P * 2304 + 512) + 4096, NP * (P * 2304 + 512), P * 2304 + 512, 2304)
+    page_major = (2 * P * row, P * row, 2 * 2 * P * row, row)                # pages outermost
+    for st in (good, padded, page_major):
+        kvx.kvx_plan(None, None, kvx.pool_desc(2, 8, 128, 2, P, NP, strides=st), b, 0, 2).destroy()
+    bad = {
+        "pages overlap": (good[0], good[1], (P - 1) * row, row),
+        "K and V overlap": (good[0], good[1] - 16, good[2], good[3]),
+        "layers overlap": (good[1], good[1], good[2], good[3]),
+        "layers inside a page": (16 * 1024, good[1], good[2], good[3]),
+        "page stride below one row": (good[0], good[1], 1024, row),
+    }
+    for what, st in bad.items():
+        recv = kvx.pool_desc(2, 8, 128, 2, P, NP, strides=st)
+        with pytest.raises(kvx.KvxError) as e:
+            kvx.kvx_plan(None, None, recv, b, 0, 2)
+        assert e.value.status == kvx.ERR_INVALID_ARG, what
+        with pytest.raises(kvx.KvxError) as e:
+            kvx.kvx_plan_workspace_bytes(None, None, recv, b)
+        assert e.value.status == kvx.ERR_INVALID_ARG, what
+        kvx.kvx_plan(recv, b, None, None, 0, 2).destroy()                    # as a sender: allowed
+    # an axis of extent 1 has no say: one layer, any layer stride
+    one_layer = kvx.pool_desc(1, 8, 128, 2, P, NP, strides=(16, good[1], good[2], good[3]))
+    kvx.kvx_plan(None, None, one_layer, b, 0, 1).destroy()
+
+
+def test_release_cached_with_nothing_cached():
+    assert kvx.kvx_release_cached() == 0
+
+
 def test_sides_must_agree():
     s, b = _simple()
     d_heads = kvx.pool_desc(2, 4, 128, 2, 16, 64)
@@ -237,9 +272,18 @@ def test_no_library_no_result(monkeypatch, tmp_path):
         kvx.kvx_plan_workspace_bytes(sp, sb, None, None)
     with pytest.raises(RuntimeError, match="hipcc is not here"):
         kvx.kvx_plan(sp, sb, None, None, 0, 2)
-    # a file that is not a loadable library fails just as loudly
-    bad = tmp_path / "libkvx_broken.so"
-    bad.write_bytes(b"not an ELF file")
-    monkeypatch.setattr(B, "LIB", str(bad))
-    with pytest.raises(OSError):
-        kvx.kvx_plan_workspace_bytes(sp, sb, None, None)
+    # a file that was not built from the sources beside it (no id, or another id) is not loaded either:
+    # the binding asks for a rebuild, and fails as loudly when there is no compiler
+    for blob in (b"not an ELF file", B.ID_TAG.encode() + b"0" * 32):
+        bad = tmp_path / "libkvx_stale.so"
+        bad.write_bytes(blob)
+        monkeypatch.setattr(B, "LIB", str(bad))
+        assert B.is_stale()
+        with pytest.raises(RuntimeError, match="hipcc is not here"):
+            kvx.kvx_plan_workspace_bytes(sp, sb, None, None)
+
+
+def test_built_library_names_its_sources():
+    from paper_2408_08147_amd import build as B
+    assert not B.is_stale()
+    assert kvx.kvx_build_id() == B.ID_TAG + B.source_id()
