@@ -9,6 +9,10 @@
   retrieval asynchronous retrieval (section 3.6): requests arriving one by one through k receive slots
   overlap  RecvScatter beside a stand-in for the running model (GEMMs on another stream), grid capped or not
   slice    a head slice of a wider sender pool through explicit strides (unequal tensor-parallel degrees)
+  ops      every operation of a workload by itself, a few launches in a row each (pack, unpack, convert, then
+           the plain contiguous copy of as many bytes): under a hardware-counter run the dispatches come in
+           exactly that order, so each counter reading can be given to its operation; `--sorted` first sorts
+           the page ids of the named side(s), which keeps the sizes and makes that side's chunks near-sequential
   layouts  pools whose pages are head-major or keep the token axis inside 16-byte groups of the head
            dimension, against plain [token][head][dim] pages of the same shape
 """
@@ -283,18 +287,50 @@ def study_slice(args):
                       "pack_hbm_GBps": g(tp), "unpack_hbm_GBps": g(tu), "convert_hbm_GBps": g(tc)}), flush=True)
 
 
+def study_ops(args):
+    import numpy as np
+    s = bench.Setup(args.workload, fill=False)
+    kvx, b = s.kvx, s.batch
+    if "s" in args.sorted:
+        b.ids_s = np.sort(b.ids_s)
+        s.sb = kvx.BatchDesc(b.seq_lens, b.ids_s, b.offs_s)
+    if "d" in args.sorted:
+        b.ids_d = np.sort(b.ids_d)
+        s.db = kvx.BatchDesc(b.seq_lens, b.ids_d, b.offs_d)
+    p = s.plan()
+    n = args.reps
+    half = min(s.payload, 4 << 30) // 4096 * 4096
+    assert s.src.numel() >= half and s.dst.numel() >= half
+    order = [("pack", lambda: s.pack(p)), ("unpack", lambda: s.unpack(p)), ("convert", lambda: s.convert(p)),
+             ("plain_copy", lambda: kvx.kvx_copy_yardstick(s.dst.data_ptr(), s.src.data_ptr(), half,
+                                                            s.stream.cuda_stream))]
+    out = {"study": "ops", "workload": f"{s.w.index}:{s.w.name}", "sorted_sides": args.sorted, "launches_each": n + 1,
+           "order": [name for name, _ in order], "payload_bytes": s.payload, "plain_copy_bytes": half}
+    for name, fn in order:
+        ms = s.time_op(fn, iters=n, warmup=1)
+        nbytes = half if name == "plain_copy" else s.payload
+        out[name + "_ms"] = round(ms, 4)
+        out[name + "_hbm_GBps"] = round(2 * nbytes / ms / 1e6, 1)
+    p.destroy()
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval", "slice", "overlap"])
+    ap.add_argument("study", choices=["blocks", "layers", "layouts", "retrieval", "slice", "overlap", "ops"])
     ap.add_argument("--requests", type=int, default=512, help="retrieval: requests of the workload-5 shape")
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 5])
     ap.add_argument("--layers", type=int, default=8, help="blocks: layers of the workload-2 shape to move")
+    ap.add_argument("--reps", type=int, default=4, help="ops: timed launches per operation (after one warm-up)")
+    ap.add_argument("--sorted", default="", choices=["", "s", "d", "sd"],
+                    help="ops: sort the page ids of the sender (s) and/or receiver (d) side first")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench_studies.py: no GPU visible")
     {"blocks": study_blocks, "layers": study_layers, "layouts": study_layouts,
-     "retrieval": study_retrieval, "slice": study_slice, "overlap": study_overlap}[args.study](args)
+     "retrieval": study_retrieval, "slice": study_slice, "overlap": study_overlap,
+     "ops": study_ops}[args.study](args)
 
 
 if __name__ == "__main__":

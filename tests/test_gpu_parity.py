@@ -333,6 +333,34 @@ def test_runtime_argument_errors():
     plan.destroy()
 
 
+def test_convert_between_overlapping_dense_pools_is_refused():
+    """Two pools with derived strides have known extents: a convert whose pools share bytes is turned down
+    before anything is launched, in either order, and one whose pools only touch end to end is not."""
+    import torch
+    rng = np.random.default_rng(11)
+    case = G.make_case(rng, 2, 2, 64, 2, [40, 9], 16, 8, LM, PM)
+    dev = torch.device("cuda:0")
+    sp, dp = case.kvx_pool(case.s), case.kvx_pool(case.d)
+    sb = kvx.BatchDesc(case.seq_lens, case.ids_s, case.offs_s)
+    db = kvx.BatchDesc(case.seq_lens, case.ids_d, case.offs_d)
+    nws = kvx.kvx_plan_workspace_bytes(sp, sb, dp, db)
+    ns, nd = case.pool_bytes(case.s), case.pool_bytes(case.d)
+    ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+    arena = torch.full((ns + nd,), G.CANARY_POOL, dtype=torch.uint8, device=dev)
+    plan = kvx.kvx_plan(sp, sb, dp, db, 0, 2, ws.data_ptr(), nws)
+    a = arena.data_ptr()
+    for src, dst in ((a, a), (a, a + ns - 16), (a + nd - 16, a), (a + 16, a)):
+        with pytest.raises(kvx.KvxError) as e:
+            kvx.kvx_convert(plan, src, dst)
+        assert e.value.status == kvx.ERR_INVALID_ARG, (src - a, dst - a)
+    torch.cuda.synchronize()
+    assert bool((arena == G.CANARY_POOL).all())
+    kvx.kvx_convert(plan, a, a + ns)          # back to back: allowed
+    kvx.kvx_convert(plan, a + nd, a)          # receiver first
+    torch.cuda.synchronize()
+    plan.destroy()
+
+
 # ------------------------------------------------------------------ extreme shapes
 def test_many_tiny_requests_and_single_token_pages():
     """40 000 requests (40 passes of the scan kernel), pages of one token, 16-byte rows."""
