@@ -368,6 +368,29 @@ kvx_status kvx_retriever_drain(kvx_retriever_t *ret);
 kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const kvx_launch_cfg *cfg,
                               void *stream);
 
+/* ---------------------------------------------------------------------------
+ * For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  RecvScatter (kvx_plan for a receiver side followed by kvx_unpack) in one
+ * call that allocates nothing, on the device or on the host: the plan's device tables live in a fixed
+ * array inside the library's device image (KVX_NOALLOC_SCRATCH_BYTES per GPU, held until the process
+ * ends), the block tables ride in a kernel's launch arguments, and no plan object is created.
+ *
+ * Same arguments, checks, results and errors as kvx_plan(NULL, NULL, d, db, layer_begin, layer_end, ...)
+ * + kvx_unpack(plan, buf, buf_bytes, dst_pool, stream), with these limits:
+ *   - num_requests + used pages (sum of ceil(seq_len/page_tokens)) <= KVX_NOALLOC_MAX_TABLE_WORDS, and the
+ *     plan's device tables <= KVX_NOALLOC_SCRATCH_BYTES: beyond either, KVX_ERR_CAPACITY and nothing is
+ *     enqueued;
+ *   - default launch configuration.
+ * Three kernel launches on `stream` (scan, fill, unpack).  Every call on a GPU uses that GPU's one
+ * scratch array: it keeps the previous call's tables, each call rewrites everything it reads, and calls
+ * on the same stream are ordered; calls that overlap on one GPU (different streams, or threads on
+ * different streams) race on the array and must be serialised by the caller. */
+#define KVX_NOALLOC_MAX_TABLE_WORDS 896u
+#define KVX_NOALLOC_SCRATCH_BYTES 65536u
+kvx_status kvx_unpack_noalloc(const kvx_pool_desc *d, const kvx_batch_desc *db, uint32_t layer_begin,
+                              uint32_t layer_end, const void *buf, uint64_t buf_bytes, void *dst_pool,
+                              void *stream);
+
 /* No passage of the paper: utility.  A string naming the sources this library was built from (a hash
  * of them, fixed at build time), so that a loader can tell a stale binary from a current one. */
 const char *kvx_build_id(void);

@@ -8,7 +8,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvx.so")
 SOURCES = [os.path.join(CSRC, "kvx_api.cpp"), os.path.join(CSRC, "kvx_retriever.cpp"),
-           os.path.join(CSRC, "kvx_kernels.hip")]
+           os.path.join(CSRC, "kvx_kernels.hip"), os.path.join(CSRC, "kvx_noalloc.hip")]
 ID_TAG = "kvx-sources:"
 HEADERS = [os.path.join(CSRC, "kvx_internal.h"), os.path.join(ROOT, "include", "kvx.h")]
 

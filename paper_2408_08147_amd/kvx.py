@@ -28,9 +28,11 @@ EXPORTS = (
     "kvx_unpack_layers", "kvx_convert_layers", "kvx_pack_blockwise", "kvx_copy_yardstick",
     "kvx_retriever_arena_bytes", "kvx_retriever_create", "kvx_retriever_destroy", "kvx_retriever_acquire",
     "kvx_retriever_scatter", "kvx_retriever_abandon", "kvx_retriever_poll", "kvx_retriever_drain",
-    "kvx_release_cached", "kvx_build_id", "kvx_status_string",
+    "kvx_unpack_noalloc", "kvx_release_cached", "kvx_build_id", "kvx_status_string",
     "kvx_last_device_error",
 )
+NOALLOC_MAX_TABLE_WORDS = 896
+NOALLOC_SCRATCH_BYTES = 65536
 
 
 class KvxError(RuntimeError):
@@ -165,6 +167,8 @@ def load():
     lib.kvx_retriever_poll.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.c_uint32, C.POINTER(C.c_uint32)]
     lib.kvx_retriever_drain.argtypes = [C.c_void_p]
     lib.kvx_copy_yardstick.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(LaunchCfg), C.c_void_p]
+    lib.kvx_unpack_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_uint64,
+                                       C.c_void_p, C.c_void_p]
     lib.kvx_release_cached.argtypes = [C.POINTER(C.c_uint64)]
     lib.kvx_build_id.restype = C.c_char_p
     lib.kvx_build_id.argtypes = []
@@ -387,6 +391,13 @@ def kvx_retriever_poll(ret: Retriever, capacity: int = 64):
 
 def kvx_retriever_drain(ret: Retriever) -> None:
     _check(load().kvx_retriever_drain(ret.handle), "kvx_retriever_drain")
+
+
+def kvx_unpack_noalloc(d: PoolDesc, db: BatchDesc, layer_begin: int, layer_end: int, buf: int, buf_bytes: int,
+                       dst_pool: int, stream: int = 0) -> None:
+    _check(load().kvx_unpack_noalloc(_ref(d), _ref(db), layer_begin, layer_end, C.c_void_p(buf or None), buf_bytes,
+                                     C.c_void_p(dst_pool or None), C.c_void_p(stream or None)),
+           "kvx_unpack_noalloc")
 
 
 def kvx_release_cached() -> int:

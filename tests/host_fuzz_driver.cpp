@@ -77,6 +77,21 @@ int main(int argc, char **argv) {
         kvx_plan_t *plan = nullptr;
         kvx_status st = kvx_plan(mode != 1 ? &s : nullptr, mode != 1 ? &sb : nullptr, mode != 0 ? &d : nullptr,
                                  mode != 0 ? &db : nullptr, l0, l1, nullptr, 0, nullptr, &plan);
+        if (mode == 1) {
+            // The entry point that allocates nothing runs the same checks on a code path of its own.  What
+            // kvx_plan refuses for a receiver it must refuse too; what kvx_plan accepts it may only turn
+            // down for its own limits, or (with no device here) at its first HIP call.
+            const kvx_status sn = kvx_unpack_noalloc(&d, &db, l0, l1, lens.data(), 1ull << 40, &d, nullptr);
+            if (st != KVX_OK && (sn == KVX_OK || sn == KVX_ERR_DEVICE)) {
+                printf("noalloc got past what kvx_plan refused (%d vs %d)\n", (int)st, (int)sn);
+                return 1;
+            }
+            if (st == KVX_OK && sn != KVX_OK && sn != KVX_ERR_DEVICE && sn != KVX_ERR_ALIGNMENT &&
+                sn != KVX_ERR_CAPACITY && sn != KVX_ERR_INVALID_ARG) {
+                printf("noalloc refused what kvx_plan accepted (%d)\n", (int)sn);
+                return 1;
+            }
+        }
         if (st != KVX_OK) {
             if (plan) { printf("plan returned on failure\n"); return 1; }
             (void)kvx_status_string(st);

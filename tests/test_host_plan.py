@@ -118,6 +118,38 @@ def test_receiver_strides_must_not_alias():
     kvx.kvx_plan(None, None, one_layer, b, 0, 1).destroy()
 
 
+def test_unpack_noalloc_refuses_on_the_host():
+    """Everything kvx_unpack_noalloc can refuse, it refuses before any HIP call."""
+    d = kvx.pool_desc(2, 8, 128, 2, 16, 4096)
+    ok = kvx.BatchDesc([100, 33], np.arange(10), [0, 7, 10])
+    f = kvx.kvx_unpack_noalloc
+    expect(kvx.ERR_INVALID_ARG, f, None, ok, 0, 2, 4096, 1 << 30, 8192)
+    expect(kvx.ERR_INVALID_ARG, f, d, None, 0, 2, 4096, 1 << 30, 8192)
+    expect(kvx.ERR_INVALID_ARG, f, d, ok, 1, 0, 4096, 1 << 30, 8192)
+    expect(kvx.ERR_INVALID_ARG, f, d, ok, 0, 3, 4096, 1 << 30, 8192)
+    expect(kvx.ERR_CAPACITY, f, d, ok, 0, 2, 4096, 133 * 2 * 2 * 2048 - 1, 8192)       # buffer too small
+    expect(kvx.ERR_INVALID_ARG, f, d, ok, 0, 2, 0, 1 << 30, 8192)
+    expect(kvx.ERR_ALIGNMENT, f, d, ok, 0, 2, 4096 + 8, 1 << 30, 8192)
+    dup = kvx.BatchDesc([100, 33], [0, 1, 2, 3, 4, 5, 6, 0, 1, 9], [0, 7, 10])
+    expect(kvx.ERR_BLOCK_TABLE, f, d, dup, 0, 2, 4096, 1 << 30, 8192)
+    expect(kvx.ERR_BLOCK_TABLE, f, d, kvx.BatchDesc([100, 33], np.arange(9), [0, 6, 9]), 0, 2, 4096, 1 << 30, 8192)
+    expect(kvx.ERR_BLOCK_TABLE, f, d, kvx.BatchDesc([16], [4096], [0, 1]), 0, 2, 4096, 1 << 30, 8192)
+    # the limit: requests + used pages <= 896 words
+    n_ok, n_over = [16] * 448, [16] * 449
+    at_limit = kvx.BatchDesc(n_ok, np.arange(448), np.arange(449))
+    over = kvx.BatchDesc(n_over, np.arange(449), np.arange(450))
+    assert 2 * 448 == kvx.NOALLOC_MAX_TABLE_WORDS
+    expect(kvx.ERR_CAPACITY, f, d, over, 0, 2, 4096, 1 << 40, 8192)
+    expect(kvx.ERR_CAPACITY, f, d, kvx.BatchDesc([1] * 897, np.arange(897), np.arange(898)), 0, 2, 4096, 1 << 40, 8192)
+    # at the limit the tables fit the scratch array: the call gets past every host check (and, with no GPU
+    # here, stops at the first HIP call)
+    ws = kvx.kvx_plan_workspace_bytes(None, None, d, at_limit)
+    assert ws <= kvx.NOALLOC_SCRATCH_BYTES
+    # an empty transfer is a no-op that touches no device
+    f(d, kvx.BatchDesc([0, 0], [], [0, 0, 0]), 0, 2, 0, 0, 0)
+    f(d, ok, 1, 1, 0, 0, 0)
+
+
 def test_release_cached_with_nothing_cached():
     assert kvx.kvx_release_cached() == 0
 

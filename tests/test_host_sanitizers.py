@@ -17,6 +17,7 @@ def test_host_validation_under_asan_ubsan(tmp_path):
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
            "-I", os.path.join(ROOT, "include"), "-I", csrc,
            "-x", "hip", os.path.join(csrc, "kvx_api.cpp"), os.path.join(csrc, "kvx_kernels.hip"),
+           os.path.join(csrc, "kvx_noalloc.hip"),
            os.path.join(ROOT, "tests", "host_fuzz_driver.cpp"), "-o", str(exe)]
     build = subprocess.run(cmd, capture_output=True, text=True)
     assert build.returncode == 0, build.stderr[-3000:]

@@ -1,0 +1,74 @@
+"""kvx_unpack_noalloc, the RecvScatter for callers that cannot allocate, against kvx_plan + kvx_unpack:
+the receiver pool (live slots, dead slots, unlisted pages) must come out byte for byte the same, on calls
+in a row that share the GPU's one scratch array, each smaller than the one before."""
+import numpy as np
+import pytest
+
+from paper_2408_08147_amd import kvx
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def scatter_both_ways(rng, L, H, D, e, lens, P, layout, l0, l1, inner=0):
+    import torch
+    dev = torch.device("cuda:0")
+    lens = np.asarray(lens, dtype=np.uint32)
+    used = int(sum((int(n) + P - 1) // P for n in lens))
+    num_pages = 2 * used + 3
+    ids, offs = G.tables(rng, lens, P, num_pages, unique=True, extra=1)
+    d = kvx.pool_desc(L, H, D, e, P, num_pages, layout, inner=inner)
+    db = kvx.BatchDesc(lens, ids, offs)
+    row = H * D * e
+    total = (l1 - l0) * 2 * row * int(lens.sum())
+    pool_bytes = L * 2 * num_pages * P * row
+    st = torch.cuda.Stream(device=dev)
+    with torch.cuda.stream(st):
+        buf = torch.from_numpy(rng.integers(0, 256, size=total + 64, dtype=np.uint8)).to(dev)
+        want = torch.full((pool_bytes,), G.CANARY_POOL, dtype=torch.uint8, device=dev)
+        got = torch.full((pool_bytes,), G.CANARY_POOL, dtype=torch.uint8, device=dev)
+        nws = kvx.kvx_plan_workspace_bytes(None, None, d, db)
+        ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+        plan = kvx.kvx_plan(None, None, d, db, l0, l1, ws.data_ptr(), nws, st.cuda_stream)
+        assert kvx.kvx_plan_total_bytes(plan) == total
+        kvx.kvx_unpack(plan, buf.data_ptr(), total, want.data_ptr(), st.cuda_stream)
+        kvx.kvx_unpack_noalloc(d, db, l0, l1, buf.data_ptr(), total, got.data_ptr(), st.cuda_stream)
+    st.synchronize()
+    plan.destroy()
+    assert bool((want != G.CANARY_POOL).any()) or total == 0
+    assert torch.equal(got, want), f"receiver pools differ: {int((got != want).sum())} bytes"
+    return total
+
+
+def test_two_calls_in_a_row_second_smaller():
+    rng = np.random.default_rng(77)
+    # close to the limit of 896 table words: 300 requests and their pages
+    big = [int(x) for x in rng.integers(1, 17, size=200)] + [int(x) for x in rng.integers(17, 33, size=150)]
+    rng.shuffle(big)
+    assert len(big) + sum((n + 15) // 16 for n in big) == 850 <= kvx.NOALLOC_MAX_TABLE_WORDS
+    t1 = scatter_both_ways(rng, 4, 8, 128, 2, big, 16, 0, 0, 4)
+    t2 = scatter_both_ways(rng, 4, 8, 128, 2, [100, 1, 0, 333, 48], 16, 0, 1, 3)
+    assert t1 > t2 > 0
+    t3 = scatter_both_ways(rng, 2, 1, 128, 2, [7], 128, 1, 0, 2)
+    assert t2 > t3 > 0
+
+
+def test_page_major_and_page_arrangements():
+    rng = np.random.default_rng(78)
+    scatter_both_ways(rng, 3, 8, 128, 2, [4096, 1500, 129], 16, 1, 0, 3)          # runs kept together per page
+    scatter_both_ways(rng, 3, 4, 64, 2, [300, 77, 64], 32, 0, 0, 3, inner=2)      # through the tile kernel
+    scatter_both_ways(rng, 2, 8, 128, 1, [2000], 128, 0, 1, 2)
+
+
+def test_limits_are_errors_and_nothing_is_written():
+    import torch
+    dev = torch.device("cuda:0")
+    d = kvx.pool_desc(1, 1, 16, 1, 1, 4096)
+    over = kvx.BatchDesc([1] * 449, np.arange(449), np.arange(450))
+    buf = torch.zeros(1 << 16, dtype=torch.uint8, device=dev)
+    dst = torch.full((1 << 17,), G.CANARY_POOL, dtype=torch.uint8, device=dev)
+    with pytest.raises(kvx.KvxError) as e:
+        kvx.kvx_unpack_noalloc(d, over, 0, 1, buf.data_ptr(), 1 << 16, dst.data_ptr(), 0)
+    assert e.value.status == kvx.ERR_CAPACITY
+    torch.cuda.synchronize()
+    assert bool((dst == G.CANARY_POOL).all())
