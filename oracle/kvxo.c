@@ -37,6 +37,8 @@
  *       2  [head][dim/x][token][x]      x = 16/elem_bytes elements: the token
  *                                       axis sits inside every 16-byte group of
  *                                       the head dimension
+ *       3  [head][dim][token]           the token axis innermost, element by
+ *                                       element (a transposed page)
  *     the buffer is always [token][head][dim].
  *
  * Loops are in the order of the definition; one memcpy per token row where
@@ -51,7 +53,7 @@ typedef struct {
     uint32_t num_layers, num_kv_heads, head_dim, elem_bytes;
     uint32_t page_tokens, num_pages;
     uint32_t layout;             /* 0: [layer][K,V][page]{page}  1: [page][layer][K,V]{page} */
-    uint32_t inner;              /* arrangement inside {page}: 0, 1 or 2 as listed above */
+    uint32_t inner;              /* arrangement inside {page}: 0, 1, 2 or 3 as listed above */
     uint64_t stride_layer, stride_kv, stride_page, stride_token; /* bytes; all 0 = derive from layout */
 } kvxo_pool;
 
@@ -129,6 +131,8 @@ static uint64_t elem_addr(const place *w, const kvxo_pool *g, uint32_t h, uint32
         uint64_t x = 16 / e;
         return w->base + ((h * (D / x) + d / x) * P + w->slot) * 16 + (d % x) * e;
     }
+    if (w->pool->inner == 3)                             /* [head][dim][token] */
+        return w->base + ((h * D + d) * P + w->slot) * e;
     uint64_t sl, sk, sp, st;                             /* [token][head][dim] */
     strides(w->pool, &sl, &sk, &sp, &st);
     return w->base + w->slot * st + (h * D + d) * e;
@@ -170,7 +174,7 @@ static uint64_t buf_addr(const kvxo_pool *p, const kvxo_batch *b, uint32_t l0, u
 
 static int inner_ok(const kvxo_pool *p)
 {
-    if (p->inner > 2) return 0;
+    if (p->inner > 3) return 0;
     if (p->inner && (p->stride_layer | p->stride_kv | p->stride_page | p->stride_token)) return 0;
     if (p->inner == 2 && (16 % p->elem_bytes || (p->head_dim * p->elem_bytes) % 16)) return 0;
     return 1;

@@ -56,7 +56,7 @@ class Pool:
     stride_page: int = 0
     stride_token: int = 0
     inner: int = 0          # arrangement inside a page: 0 [token][head][dim], 1 [head][token][dim],
-                            # 2 [head][dim/x][token][x] with x = 16/elem_bytes
+                            # 2 [head][dim/x][token][x] with x = 16/elem_bytes, 3 [head][dim][token]
 
     def c(self) -> _Pool:
         return _Pool(self.num_layers, self.num_kv_heads, self.head_dim, self.elem_bytes,

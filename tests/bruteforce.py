@@ -19,7 +19,7 @@ def table(ids, offs, r):
     return [int(x) for x in ids[int(offs[r]):int(offs[r + 1])]]
 
 
-def _page_view(flat: np.ndarray, L, NP, P, row, layout, inner, heads):
+def _page_view(flat: np.ndarray, L, NP, P, row, layout, inner, heads, elem=1):
     """The pool as an N-d array whose leading axes are (layer, kv, page) and
     whose page-internal axes are spelled as the arrangement's name says; the
     returned function picks one token row out of it as [head][dim] bytes."""
@@ -31,8 +31,11 @@ def _page_view(flat: np.ndarray, L, NP, P, row, layout, inner, heads):
     elif inner == 1:                                    # [head][token][dim]
         a = flat.reshape(*lead, heads, P, hb)
         pick = lambda pg, s: pg[:, s, :]
-    else:                                               # [head][dim/x][token][x], x elements = 16 bytes
+    elif inner == 2:                                    # [head][dim/x][token][x], x elements = 16 bytes
         a = flat.reshape(*lead, heads, hb // 16, P, 16)
+        pick = lambda pg, s: pg[:, :, s, :]
+    else:                                               # [head][dim][token], elements of `elem` bytes
+        a = flat.reshape(*lead, heads, hb // elem, P, elem)
         pick = lambda pg, s: pg[:, :, s, :]
     if layout == LAYER_MAJOR:
         page = lambda l, c, p: a[l, c, p]
@@ -41,15 +44,15 @@ def _page_view(flat: np.ndarray, L, NP, P, row, layout, inner, heads):
     return a, page, pick
 
 
-def flat_to_dict(flat: np.ndarray, L, NP, P, row, layout, inner=0, heads=1):
-    _, page, pick = _page_view(flat, L, NP, P, row, layout, inner, heads)
+def flat_to_dict(flat: np.ndarray, L, NP, P, row, layout, inner=0, heads=1, elem=1):
+    _, page, pick = _page_view(flat, L, NP, P, row, layout, inner, heads, elem)
     return {(l, c, p, s): bytes(np.ascontiguousarray(pick(page(l, c, p), s)).reshape(-1))
             for l in range(L) for c in range(2) for p in range(NP) for s in range(P)}
 
 
-def dict_to_flat(d: dict, L, NP, P, row, layout, inner=0, heads=1) -> np.ndarray:
+def dict_to_flat(d: dict, L, NP, P, row, layout, inner=0, heads=1, elem=1) -> np.ndarray:
     flat = np.zeros(L * 2 * NP * P * row, dtype=np.uint8)
-    a, page, pick = _page_view(flat, L, NP, P, row, layout, inner, heads)
+    a, page, pick = _page_view(flat, L, NP, P, row, layout, inner, heads, elem)
     for (l, c, p, s), v in d.items():
         tgt = pick(page(l, c, p), s)
         tgt[...] = np.frombuffer(v, dtype=np.uint8).reshape(tgt.shape)

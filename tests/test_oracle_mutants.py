@@ -40,6 +40,14 @@ MUTANTS = {
     "split_token_outside_group": ("return w->base + ((h * (D / x) + d / x) * P + w->slot) * 16 + (d % x) * e;",
                                   "return w->base + ((h * P + w->slot) * (D / x) + d / x) * 16 + (d % x) * e;"),
     "split_lane_order_reversed": ("+ (d % x) * e;", "+ (x - 1 - d % x) * e;"),
+    "tinner_forgets_slot": ("return w->base + ((h * D + d) * P + w->slot) * e;",
+                            "return w->base + ((h * D + d) * P) * e;"),
+    "tinner_column_pitch_is_head_dim": ("return w->base + ((h * D + d) * P + w->slot) * e;",
+                                        "return w->base + ((h * D + d) * D + w->slot) * e;"),
+    "tinner_heads_innermost": ("return w->base + ((h * D + d) * P + w->slot) * e;",
+                               "return w->base + ((d * g->num_kv_heads + h) * P + w->slot) * e;"),
+    "tinner_slot_not_scaled_by_element": ("return w->base + ((h * D + d) * P + w->slot) * e;",
+                                          "return w->base + ((h * D + d) * P) * e + w->slot;"),
     "segment_length_half": ("*len = 2 * (uint64_t)b->seq_lens[r] * row_bytes(p);",
                             "*len = (uint64_t)b->seq_lens[r] * row_bytes(p);"),
     "total_forgets_kv_factor": ("* 2\n                 * tokens_before(b, b->num_requests);",

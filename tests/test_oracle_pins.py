@@ -55,13 +55,18 @@ for L, H, D, e in [(1, 1, 3, 1), (2, 2, 4, 2), (2, 1, 8, 1)]:
             TINY.append((L, H, D, e, Ps, Pd, ls, ld))
 
 
-# page-internal arrangements (0 rows, 1 head-major, 2 token axis inside 16-byte dim groups) on either side
+# page-internal arrangements (0 rows, 1 head-major, 2 token axis inside 16-byte dim groups, 3 token axis
+# innermost element by element) on either side
 INNER = []
 for H, D, e in [(2, 16, 1), (3, 8, 2), (1, 8, 4)]:
     for Ps, Pd in [(4, 4), (2, 3), (4, 1), (3, 8)]:
         for (ls, ins), (ld, ind) in [((LM, 1), (LM, 0)), ((LM, 0), (PM, 2)), ((PM, 2), (LM, 1)),
-                                      ((PM, 1), (PM, 1)), ((LM, 2), (LM, 2)), ((LM, 0), (LM, 1))]:
+                                      ((PM, 1), (PM, 1)), ((LM, 2), (LM, 2)), ((LM, 0), (LM, 1)),
+                                      ((LM, 0), (LM, 3)), ((PM, 3), (LM, 0)), ((LM, 3), (PM, 3)),
+                                      ((PM, 2), (LM, 3)), ((LM, 3), (LM, 1))]:
             INNER.append((2, H, D, e, Ps, Pd, ls, ld, ins, ind))
+# token-innermost pages whose head dimension is not a multiple of 16 bytes (nothing in that arrangement needs it)
+INNER += [(2, 2, 3, 2, 4, 3, LM, PM, 3, 0), (1, 1, 5, 1, 3, 3, PM, LM, 0, 3), (2, 3, 3, 4, 2, 5, LM, LM, 3, 3)]
 
 
 @pytest.mark.parametrize("L,H,D,e,Ps,Pd,ls,ld,ins,ind", INNER)
@@ -84,7 +89,7 @@ def test_bruteforce_tiny(L, H, D, e, Ps, Pd, ls, ld, ins=0, ind=0):
     ids_d, offs_d = make_tables(rng, lens, Pd, NPd, unique=True, extra=1)
     bs, bd = kvxo.Batch(lens, ids_s, offs_s), kvxo.Batch(lens, ids_d, offs_d)
     src = rand_pool(rng, ps)
-    src_d = bf.flat_to_dict(src, L, NPs, Ps, row, ls, ins, H)
+    src_d = bf.flat_to_dict(src, L, NPs, Ps, row, ls, ins, H, e)
 
     for l0, l1 in [(0, L), (L - 1, L), (0, 0)]:
         want = bf.pack(src_d, Ps, lens, ids_s, offs_s, l0, l1)
@@ -97,15 +102,15 @@ def test_bruteforce_tiny(L, H, D, e, Ps, Pd, ls, ld, ins=0, ind=0):
         canary = rng.integers(0, 256, size=pd.nbytes, dtype=np.uint8)
         dst = canary.copy()
         kvxo.unpack(pd, bd, l0, l1, buf, dst)
-        dst_d = bf.flat_to_dict(canary, L, NPd, Pd, row, ld, ind, H)
+        dst_d = bf.flat_to_dict(canary, L, NPd, Pd, row, ld, ind, H, e)
         bf.unpack(want, row, dst_d, Pd, lens, ids_d, offs_d, l0, l1)
-        assert np.array_equal(dst, bf.dict_to_flat(dst_d, L, NPd, Pd, row, ld, ind, H))
+        assert np.array_equal(dst, bf.dict_to_flat(dst_d, L, NPd, Pd, row, ld, ind, H, e))
 
         dst2 = canary.copy()
         kvxo.convert(ps, bs, pd, bd, l0, l1, src, dst2)
-        dst2_d = bf.flat_to_dict(canary, L, NPd, Pd, row, ld, ind, H)
+        dst2_d = bf.flat_to_dict(canary, L, NPd, Pd, row, ld, ind, H, e)
         bf.convert(src_d, Ps, ids_s, offs_s, dst2_d, Pd, ids_d, offs_d, lens, l0, l1)
-        assert np.array_equal(dst2, bf.dict_to_flat(dst2_d, L, NPd, Pd, row, ld, ind, H))
+        assert np.array_equal(dst2, bf.dict_to_flat(dst2_d, L, NPd, Pd, row, ld, ind, H, e))
 
 
 # ---------------------------------------------------------------- 3. closed form + paper numbers
@@ -267,6 +272,7 @@ def test_inner_arrangements_reduce_to_transposes(e, D):
     rows = kvxo.Pool(L, H, D, e, P, NP, LM, inner=0)
     heads = kvxo.Pool(L, H, D, e, P, NP, LM, inner=1)
     split = kvxo.Pool(L, H, D, e, P, NP, LM, inner=2)
+    tinner = kvxo.Pool(L, H, D, e, P, NP, LM, inner=3)
     src = rand_pool(rng, rows)
     b = kvxo.Batch([NP * P], np.arange(NP, dtype=np.uint32), [0, NP])
     as_elems = src.reshape(L, 2, NP, P, H, D // x, x * e)           # [token][head][dim/x][x]
@@ -279,13 +285,22 @@ def test_inner_arrangements_reduce_to_transposes(e, D):
     back = np.zeros(rows.nbytes, dtype=np.uint8)
     kvxo.convert(split, b, rows, b, 0, L, want_split, back)
     assert np.array_equal(back, src)
-    # pack out of either arrangement gives the same buffer as out of rows
+    # token axis innermost: [token][head][dim][e] -> [head][dim][token][e], a transposed page
+    by_elem = src.reshape(L, 2, NP, P, H, D, e)
+    want_tinner = np.ascontiguousarray(by_elem.transpose(0, 1, 2, 4, 5, 3, 6)).reshape(-1)
+    kvxo.convert(rows, b, tinner, b, 0, L, src, out)
+    assert np.array_equal(out, want_tinner)
+    kvxo.convert(split, b, tinner, b, 0, L, want_split, out)
+    assert np.array_equal(out, want_tinner)
+    kvxo.convert(tinner, b, rows, b, 0, L, want_tinner, back)
+    assert np.array_equal(back, src)
+    # pack out of any arrangement gives the same buffer as out of rows
     bufs = []
-    for pool, data in ((rows, src), (split, want_split)):
+    for pool, data in ((rows, src), (split, want_split), (tinner, want_tinner)):
         buf = np.zeros(kvxo.total_bytes(pool, b, 0, L), dtype=np.uint8)
         kvxo.pack(pool, b, 0, L, data, buf)
         bufs.append(buf)
-    assert np.array_equal(bufs[0], bufs[1])
+    assert np.array_equal(bufs[0], bufs[1]) and np.array_equal(bufs[0], bufs[2])
     with pytest.raises(ValueError):                                  # 16-byte groups need head_dim*e % 16 == 0
         kvxo.pack(kvxo.Pool(1, 1, 4, 2, 4, 2, LM, inner=2), kvxo.Batch([1], [0], [0, 1]), 0, 1,
                   np.zeros(64, np.uint8), np.zeros(64, np.uint8))
