@@ -104,14 +104,14 @@ def study_layers(args):
 
 def study_layouts(args):
     from paper_2408_08147_amd import workloads as W
-    names = {0: "rows", 1: "head_major", 2: "dim_split_token"}
+    names = {0: "rows", 1: "head_major", 2: "dim_split_token", 3: "token_innermost"}
     shapes = [("workload2 shape, 128-token pages", W.CONFIGS[2], {}),
               ("workload2 shape, 16-token pages", W.CONFIGS[2], dict(page_s=16, page_d=16)),
               ("workload2 shape, 128 -> 16 tokens, page-major receiver", W.CONFIGS[2],
                dict(page_d=16, layout_d=W.PAGE_MAJOR)),
               ("workload3 shape (one head, 256-byte rows)", W.CONFIGS[3], {})]
     for label, base, kw in shapes:
-        for ins, ind in [(0, 0), (0, 1), (1, 0), (0, 2), (2, 0), (2, 2), (1, 2)]:
+        for ins, ind in [(0, 0), (0, 1), (1, 0), (0, 2), (2, 0), (2, 2), (1, 2), (0, 3), (3, 0), (3, 3), (2, 3)]:
             w = base.scaled(inner_s=ins, inner_d=ind, **kw)
             s = bench.Setup(w, fill=False)
             p = s.plan()

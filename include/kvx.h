@@ -18,8 +18,9 @@
  *     The library owns the host-side plan objects and, for batches whose tables
  *     do not fit a kernel's launch arguments, a few pinned host blocks that
  *     kvx_plan stages those tables in: they are created on first need
- *     (hipHostMalloc and an event), handed from plan to plan, kept at a count of
- *     at most 8 idle ones, and freed by kvx_release_cached.  Host arrays handed
+ *     (hipHostMalloc and an event), handed from plan to plan, trimmed back to 32
+ *     idle ones whenever more than 64 have piled up, and freed by
+ *     kvx_release_cached.  Host arrays handed
  *     to kvx_plan are copied before it returns.
  *   - pack / unpack / convert enqueue work on `stream` and return; they never
  *     synchronise and never allocate device memory.  Each is one kernel launch
@@ -85,13 +86,19 @@ typedef enum {
 
 /* Arrangement of the page_tokens tokens inside one {page} (one layer, K or V).
  * The receiver restores "desired discrete blocks" (sections 1 and 2.2.3); the
- * paper fixes no block-internal layout, so three are offered.  The contiguous
+ * paper fixes no block-internal layout, so four are offered.  The contiguous
  * buffer is always [token][head][dim]. */
 typedef enum {
     KVX_INNER_TOKEN_ROWS = 0,      /* [token][head][dim]: a token row is contiguous */
     KVX_INNER_HEAD_MAJOR = 1,      /* [head][token][dim] */
-    KVX_INNER_DIM_SPLIT_TOKEN = 2  /* [head][dim/x][token][x], x = 16/elem_bytes elements: the token axis sits
+    KVX_INNER_DIM_SPLIT_TOKEN = 2, /* [head][dim/x][token][x], x = 16/elem_bytes elements: the token axis sits
                                       inside every 16-byte group of the head dimension */
+    KVX_INNER_TOKEN_INNERMOST = 3  /* [head][dim][token]: the token axis innermost element by element, a
+                                      transposed page (the shape of a V cache read along the tokens).  Bytes
+                                      change place below the 16-byte grain here, so tiles are transposed
+                                      through LDS at element granularity.  Fast when page_tokens*elem_bytes is
+                                      a multiple of 16 (columns then start on 16-byte boundaries); any other
+                                      page size works, element by element */
 } kvx_inner;
 
 /* Geometry of one paged pool (section 2.2.3, "Block-fixed Management": device
@@ -107,9 +114,10 @@ typedef struct {
     uint32_t page_tokens;  /* tokens per page (block) */
     uint32_t num_pages;    /* pages in the pool */
     uint32_t layout;       /* kvx_layout */
-    uint32_t inner;        /* kvx_inner; anything but TOKEN_ROWS needs the derived (all-zero) strides,
-                              head_dim*elem_bytes a multiple of 16, and for DIM_SPLIT_TOKEN elem_bytes
-                              dividing 16 */
+    uint32_t inner;        /* kvx_inner; anything but TOKEN_ROWS needs the derived (all-zero) strides;
+                              HEAD_MAJOR and DIM_SPLIT_TOKEN need head_dim*elem_bytes a multiple of 16,
+                              DIM_SPLIT_TOKEN elem_bytes dividing 16, TOKEN_INNERMOST elem_bytes of 1, 2, 4
+                              or 8 */
     uint64_t stride_layer, stride_kv, stride_page, stride_token;
 } kvx_pool_desc;
 

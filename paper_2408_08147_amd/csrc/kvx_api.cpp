@@ -30,9 +30,11 @@ namespace {
 // recorded behind the H2D copy that reads it; it is handed out again, or freed,
 // only once that event has completed, so a plan destroyed with work still
 // queued never has its staged tables overwritten or unmapped before they were
-// copied.  The list keeps at most kPinnedKeep blocks whose copies are done;
-// kvx_release_cached frees those on request.
-constexpr size_t kPinnedKeep = 8;
+// copied.  Freeing and re-creating a block costs about a millisecond, so the
+// list is trimmed with hysteresis: once it holds more than 2 * kPinnedKeep
+// blocks, those whose copies are done are freed down to kPinnedKeep.
+// kvx_release_cached frees every idle block on request.
+constexpr size_t kPinnedKeep = 32;
 std::mutex g_pinned_mu;
 std::vector<PinnedBlock> g_pinned_free;
 
@@ -100,7 +102,7 @@ void pinned_release(PinnedBlock b) {
     if (!b.ptr) return;
     std::lock_guard<std::mutex> lk(g_pinned_mu);
     g_pinned_free.push_back(b);
-    if (g_pinned_free.size() > kPinnedKeep) (void)pinned_trim(kPinnedKeep);
+    if (g_pinned_free.size() > 2 * kPinnedKeep) (void)pinned_trim(kPinnedKeep);
 }
 
 } // namespace
@@ -126,7 +128,7 @@ static bool strides_nest(const kvx_pool_desc *d, uint64_t row) {
 
 kvx_status resolve_pool(const kvx_pool_desc *d, bool receiver, Geometry *g) {
     if (!d->num_layers || !d->num_kv_heads || !d->head_dim || !d->elem_bytes || !d->page_tokens ||
-        !d->num_pages || d->inner > KVX_INNER_DIM_SPLIT_TOKEN)
+        !d->num_pages || d->inner > KVX_INNER_TOKEN_INNERMOST)
         return KVX_ERR_INVALID_ARG;
     g->present = true;
     g->desc = *d;
@@ -138,7 +140,12 @@ kvx_status resolve_pool(const kvx_pool_desc *d, bool receiver, Geometry *g) {
     if (d->inner != KVX_INNER_TOKEN_ROWS) {
         const uint64_t head_bytes = (uint64_t)d->head_dim * d->elem_bytes;
         if (any) return KVX_ERR_INVALID_ARG;
-        if (head_bytes % 16) return KVX_ERR_ALIGNMENT;
+        if (d->inner == KVX_INNER_TOKEN_INNERMOST) {
+            if (d->elem_bytes != 1 && d->elem_bytes != 2 && d->elem_bytes != 4 && d->elem_bytes != 8)
+                return KVX_ERR_INVALID_ARG;
+        } else if (head_bytes % 16) {
+            return KVX_ERR_ALIGNMENT;
+        }
         if (d->inner == KVX_INNER_DIM_SPLIT_TOKEN && 16 % d->elem_bytes) return KVX_ERR_INVALID_ARG;
     }
     if (any) {
@@ -183,6 +190,10 @@ kvx_status resolve_pool(const kvx_pool_desc *d, bool receiver, Geometry *g) {
         g->upg = 1;
         g->granule_step = 16ull * d->page_tokens;
         g->token_fast = true;
+    } else if (d->inner == KVX_INNER_TOKEN_INNERMOST) {
+        g->token_step = d->elem_bytes;
+        g->token_innermost = true;
+        g->column_step = d->page_tokens * d->elem_bytes; // below 2^32: page_tokens * row is
     }
     // last byte of the last row, one past: pages of every arrangement hold page_tokens * row bytes
     {
@@ -701,6 +712,79 @@ kvx_status run_xpose(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, co
     return hip_ok(e, "xpose_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
 }
 
+ElemSide elem_side(const Geometry &g, bool is_buf, uint64_t row) {
+    ElemSide x{};
+    x.is_buf = is_buf;
+    if (is_buf) {
+        x.token_step = row;
+        x.units_per_granule = (uint32_t)(row / 16);
+    } else {
+        x.stride_layer = g.sl;
+        x.stride_kv = g.sk;
+        x.token_step = g.token_step;
+        x.granule_step = g.granule_step;
+        x.units_per_granule = g.upg;
+        x.column_step = g.column_step;
+    }
+    x.granule_magic = x.units_per_granule > 1 ? (uint32_t)((1ull << 32) / x.units_per_granule) + 1u : 0u;
+    return x;
+}
+
+// The same again for a pool with the token axis innermost on either side: tiles transposed at element
+// granularity through LDS.
+kvx_status run_xpose_elem(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, const void *src, void *dst,
+                          void *stream) {
+    const OpShape &o = plan->z.ops[op];
+    const kvx_launch_cfg &c = plan->launch;
+    const Geometry &gs = plan->s, &gd = plan->d;
+    ElemParams ep{};
+    ep.runs = reinterpret_cast<const kvx_run *>(plan->ws + plan->z.off_runs[op]);
+    ep.src = static_cast<const char *>(src);
+    ep.dst = static_cast<char *>(dst);
+    ep.s = elem_side(gs, op == OP_UNPACK, plan->row);
+    ep.d = elem_side(gd, op == OP_PACK, plan->row);
+    const int sk = op == OP_UNPACK ? 0 : (gs.token_innermost ? 2 : (gs.token_fast ? 1 : 0));
+    const int dk = op == OP_PACK ? 0 : (gd.token_innermost ? 2 : (gd.token_fast ? 1 : 0));
+    const uint32_t elem = (op == OP_UNPACK ? gd : gs).desc.elem_bytes; // the two sides agree
+    ep.row = (uint32_t)plan->row;
+    ep.units_per_row = (uint32_t)(plan->row / 16);
+    ep.layer_begin = plan->l0;
+    ep.lc_first = 2 * (lb - plan->l0);
+    ep.num_lc = 2 * (le - lb);
+    ep.num_runs = (uint32_t)o.num_runs;
+    // A tile is 16 KiB: as many tokens as a run can have (long pieces along the token axis are what the
+    // token-innermost side writes contiguously), between 16 and 256, and the rest along the row.
+    const uint32_t max_tokens = o.max_run_bytes / ep.row;
+    ep.log2_tt = 4;
+    while (ep.log2_tt < 8 && (1u << ep.log2_tt) < max_tokens) ++ep.log2_tt;
+    ep.log2_wu = 10 - ep.log2_tt;
+    ep.tiles_t = (max_tokens + (1u << ep.log2_tt) - 1) >> ep.log2_tt;
+    ep.tiles_w = (ep.units_per_row + (1u << ep.log2_wu) - 1) >> ep.log2_wu;
+    const uint64_t total = (uint64_t)ep.num_lc * ep.num_runs * ep.tiles_t * ep.tiles_w;
+    if (total >= (1ull << 32)) return KVX_ERR_UNSUPPORTED;
+    ep.total_tiles = (uint32_t)total;
+    ep.order = c.order == 3 ? 1u : c.order;
+    if (!ep.order)
+        ep.order = (op != OP_PACK && !gd.custom_strides && gd.desc.layout == KVX_LAYOUT_PAGE_MAJOR) ? 2 : 1;
+    ep.group = o.group_slots;
+    const uint32_t grid_cap = std::min<uint32_t>(c.max_workgroups, (1u << 31) / kElemThreads - 8u);
+    uint32_t grid = std::min(ep.total_tiles, grid_cap);
+    if (c.xcd_swizzle == 2) {
+        grid = (grid + 7u) / 8u * 8u;
+        ep.swizzle_chunk = grid / 8u;
+    }
+    const int nt = c.nontemporal == 1 ? 0 : 1; // default policy only on request; agent-scope stores are not offered here
+    // A token-innermost side whose runs are shorter than its pages (the other side's pages are finer) hands
+    // every tile pieces of a column that are shorter than a 128-byte line; the rest of each line belongs to
+    // the neighbouring runs of the same page, whose tiles come next.  Accesses that may stay in the L2 let
+    // those find the line there: a line is fetched once instead of once per piece, and written back whole
+    // instead of piece by piece (measured on 128 <-> 16 tokens: reads 4.1 -> 5.2 TB/s, writes 1.4 -> ?).
+    ep.cached_loads = (sk == 2 && (uint64_t)max_tokens * elem < 128u && max_tokens < gs.desc.page_tokens) ? 1u : 0u;
+    ep.cached_stores = (dk == 2 && (uint64_t)max_tokens * elem < 128u && max_tokens < gd.desc.page_tokens) ? 1u : 0u;
+    hipError_t e = launch_xpose_elem(ep, elem, sk, dk, nt, grid, static_cast<hipStream_t>(stream));
+    return hip_ok(e, "xpose_elem_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
+}
+
 // Launches one operation over layers [lb, le) of the plan's range.  Buffer offsets stay those of the
 // plan's whole range, so a sub-range touches exactly its own segments of the same buffer.
 } // namespace
@@ -721,6 +805,8 @@ kvx_status kvx::run_op(const kvx_plan_s *plan, Op op, uint32_t lb, uint32_t le, 
     const kvx_launch_cfg &c = plan->launch;
     const bool src_rows = (op == OP_UNPACK) || plan->s.dense_rows;
     const bool dst_rows = (op == OP_PACK) || plan->d.dense_rows;
+    if ((op != OP_UNPACK && plan->s.token_innermost) || (op != OP_PACK && plan->d.token_innermost))
+        return run_xpose_elem(plan, op, lb, le, src, dst, stream);
     if (!src_rows || !dst_rows) return run_xpose(plan, op, lb, le, src, dst, stream);
     CopyParams cp{};
     cp.runs = reinterpret_cast<const kvx_run *>(plan->ws + plan->z.off_runs[op]);
@@ -773,6 +859,12 @@ kvx_status kvx::run_op(const kvx_plan_s *plan, Op op, uint32_t lb, uint32_t le, 
         cp.swizzle_chunk = grid / 8u;
         cp.swizzle_block = c.xcd_block_tiles;
     }
+    cp.by_tiles_per_run = make_fast_div(cp.tiles_per_run);
+    cp.by_num_runs = make_fast_div(cp.num_runs);
+    cp.by_runs_per_part = make_fast_div(cp.runs_per_part);
+    cp.by_group = make_fast_div(cp.group);
+    cp.by_num_lc = make_fast_div(cp.num_lc);
+    cp.by_swizzle_block = make_fast_div(cp.swizzle_block);
     // Bytes in flight: the large tiles of order 2 fill a compute unit with 128 KiB of loads when as many
     // workgroups as fit are resident; measured, 32 KiB per compute unit (8 MB over the device, what the
     // small tiles of the other orders have anyway) is 3 % faster.  Unless the caller chose a tile or a cap.

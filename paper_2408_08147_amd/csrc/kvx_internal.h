@@ -75,6 +75,30 @@ struct FillParams {
     kvx_run *runs[NUM_OPS];
 };
 
+// Division of any 32-bit n by a fixed divisor d >= 1 as a multiply-high and two shifts (Granlund and
+// Montgomery's round-up method), the constants worked out once on the host: the data movers split a flat
+// tile index by several run-time divisors per tile, and the hardware has no integer divide.
+struct FastDiv {
+    uint32_t d, mul, sh1, sh2;
+};
+inline FastDiv make_fast_div(uint32_t d) {
+    FastDiv f{d ? d : 1u, 0, 0, 0};
+    uint32_t l = 0;
+    while (l < 32 && (1ull << l) < f.d) ++l;                       // l = ceil(log2 d)
+    f.mul = (uint32_t)((((1ull << l) - f.d) << 32) / f.d + 1ull);
+    f.sh1 = l < 1 ? l : 1;
+    f.sh2 = l ? l - 1 : 0;
+    return f;
+}
+__host__ __device__ inline uint32_t fast_div(uint32_t n, const FastDiv &f) {
+#ifdef __HIP_DEVICE_COMPILE__
+    const uint32_t t = __umulhi(f.mul, n);
+#else
+    const uint32_t t = (uint32_t)(((uint64_t)f.mul * n) >> 32);
+#endif
+    return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
+
 struct CopyParams {
     const kvx_run *runs;
     const char *src;
@@ -94,6 +118,7 @@ struct CopyParams {
     uint32_t group;           // order 2: consecutive runs that stay together inside one (layer,kv)
     uint32_t swizzle_chunk;   // 0 = off, else tiles per XCD (grid is a multiple of 8)
     uint32_t swizzle_block;   // 0 = eighths of the grid, else tiles per block dealt round-robin to the XCDs
+    FastDiv by_tiles_per_run, by_num_runs, by_runs_per_part, by_group, by_num_lc, by_swizzle_block;
 };
 
 // One side of the tile-transposing kernel.  A row is row/16 units of 16 bytes; unit u of the token in
@@ -124,6 +149,45 @@ struct XposeParams {
     uint32_t order, group;
     uint32_t swizzle_chunk;
 };
+
+// One side of the element-transposing kernel: either addressed by 16-byte units like XposeSide (kind 0:
+// consecutive units of a token are nearest, kind 1: consecutive tokens of a unit are), or token-innermost
+// (kind 2): element (column j of the row, token t of the run) at run_offset + j*column_step + t*elem_bytes.
+struct ElemSide {
+    uint64_t stride_layer, stride_kv; // pool side only
+    uint64_t token_step;
+    uint64_t granule_step;
+    uint32_t units_per_granule;
+    uint32_t granule_magic;
+    uint32_t column_step;             // kind 2: page_tokens * elem_bytes
+    uint32_t is_buf;
+};
+
+struct ElemParams {
+    const kvx_run *runs;
+    const char *src;
+    char *dst;
+    ElemSide s, d;
+    uint32_t row;
+    uint32_t units_per_row;
+    uint32_t layer_begin, lc_first, num_lc;
+    uint32_t num_runs;
+    uint32_t log2_tt, log2_wu;        // tile = 2^log2_tt tokens x 2^log2_wu 16-byte units of the row = 16 KiB
+    uint32_t tiles_t, tiles_w;
+    uint32_t total_tiles;
+    uint32_t order, group;
+    uint32_t swizzle_chunk;
+    uint32_t cached_loads;            // 1: loads keep the default cache policy whatever the kernel's own is
+    uint32_t cached_stores;           // 1: the same for stores
+};
+
+constexpr uint32_t kElemThreads = 256;
+constexpr uint32_t kElemCells = 1024;   // 16-byte units per tile
+constexpr uint32_t kElemMaxTokens = 256; // tokens per tile at most (rows of 64 bytes per tile at least)
+
+// elem_bytes in {1,2,4,8}; kinds as in ElemSide, at least one of them 2; nontemporal 0 or 1.
+hipError_t launch_xpose_elem(const ElemParams &p, uint32_t elem_bytes, int src_kind, int dst_kind, int nontemporal,
+                             uint32_t grid, hipStream_t stream);
 
 constexpr uint32_t kXposeThreads = 256;
 constexpr uint32_t kXposeCells = 1024; // 16-byte units per tile (16 KiB)
@@ -170,6 +234,8 @@ struct Geometry {
     uint64_t token_step = 0, granule_step = 0;
     uint32_t upg = 0;
     bool token_fast = false;                 // consecutive tokens are nearer than consecutive units
+    bool token_innermost = false;            // [head][dim][token]: addressed by elements, not by 16-byte units
+    uint32_t column_step = 0;                // then: bytes from one (head,dim) column to the next
     uint64_t span = 0;                       // bytes from the pool's base to the end of its last row
     uint64_t used_pages = 0;                 // sum over requests of ceil(n/P)
 };

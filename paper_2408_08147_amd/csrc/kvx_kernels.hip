@@ -22,6 +22,10 @@
 //                sliced rows): tiles of tokens x 16-byte units, staged through
 //                LDS when one side is contiguous along the row and the other
 //                along the tokens.
+//   xpose_elem_kernel  the same once more for pages that keep the token axis
+//                innermost element by element ([head][dim][token]): there bytes
+//                change place below the 16-byte grain, and the tile is
+//                transposed in LDS one element at a time.
 #include <algorithm>
 #include <atomic>
 
@@ -276,6 +280,20 @@ __device__ __forceinline__ void st16(char *p, u32x4 v) {
     else *reinterpret_cast<u32x4 *>(p) = v;
 }
 
+// One run record, fetched as a single 32-byte load from a wave-uniform address.
+__device__ __forceinline__ kvx_run load_run(const kvx_run *p) {
+    using u32x8 = uint32_t __attribute__((ext_vector_type(8)));
+    const u32x8 w = __builtin_nontemporal_load(reinterpret_cast<const u32x8 *>(p));
+    kvx_run r;
+    r.src_off = ((uint64_t)w[1] << 32) | w[0];
+    r.dst_off = ((uint64_t)w[3] << 32) | w[2];
+    r.bytes = w[4];
+    r.seq_len = w[5];
+    r.request = w[6];
+    r.token = w[7];
+    return r;
+}
+
 template <int T, int U, int NT>
 __global__ __launch_bounds__(T) void copy_kernel(const kvx_run *__restrict__ runs, const char *__restrict__ src,
                                                  char *__restrict__ dst, CopyParams p) {
@@ -287,7 +305,8 @@ __global__ __launch_bounds__(T) void copy_kernel(const kvx_run *__restrict__ run
     uint32_t first = blockIdx.x;
     if (p.swizzle_block) {
         const uint32_t j = blockIdx.x >> 3, k = blockIdx.x & 7u;
-        first = (j / p.swizzle_block) * (8u * p.swizzle_block) + k * p.swizzle_block + (j % p.swizzle_block);
+        const uint32_t jb = fast_div(j, p.by_swizzle_block);
+        first = jb * (8u * p.swizzle_block) + k * p.swizzle_block + (j - jb * p.swizzle_block);
     } else if (p.swizzle_chunk) {
         first = (blockIdx.x & 7u) * p.swizzle_chunk + (blockIdx.x >> 3);
     }
@@ -304,23 +323,26 @@ __global__ __launch_bounds__(T) void copy_kernel(const kvx_run *__restrict__ run
             part = v & 7u;
             v >>= 3;
         }
-        const uint32_t s = v % p.tiles_per_run;
-        const uint32_t q = v / p.tiles_per_run;
+        const uint32_t q = fast_div(v, p.by_tiles_per_run);
+        const uint32_t s = v - q * p.tiles_per_run;
         if (p.order == 3) {
-            e = part * p.runs_per_part + q % p.runs_per_part;
-            lc = q / p.runs_per_part;
+            lc = fast_div(q, p.by_runs_per_part);
+            e = part * p.runs_per_part + (q - lc * p.runs_per_part);
             if (e >= p.num_runs) continue; // the last part may be short
         } else if (p.order == 2) {
-            const uint32_t i = q % p.group;
-            const uint32_t q2 = q / p.group;
-            lc = q2 % p.num_lc;
-            e = (q2 / p.num_lc) * p.group + i;
+            const uint32_t q2 = fast_div(q, p.by_group);
+            const uint32_t i = q - q2 * p.group;
+            const uint32_t g = fast_div(q2, p.by_num_lc);
+            lc = q2 - g * p.num_lc;
+            e = g * p.group + i;
         } else {
-            e = q % p.num_runs;
-            lc = q / p.num_runs;
+            lc = fast_div(q, p.by_num_runs);
+            e = q - lc * p.num_runs;
         }
         lc += p.lc_first;
-        const kvx_run run = runs[e];
+        // the whole 32-byte record in one scalar load (field by field the compiler fetches it in three
+        // dependent steps, each a round trip to the scalar cache or beyond)
+        const kvx_run run = load_run(runs + e);
         const uint32_t base = s * kTile;
         if (base >= run.bytes) continue;
         const uint32_t rem = run.bytes - base;
@@ -452,6 +474,203 @@ __global__ __launch_bounds__(kXposeThreads) void xpose_kernel(const kvx_run *__r
             }
             __syncthreads(); // the next tile of this workgroup reuses the stage
         }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// xpose_elem: a side whose pages keep the token axis innermost, element by element
+// ---------------------------------------------------------------------------
+// [head][dim][token] pages: element (column j of the row, token t) sits at j*column_step + t*E, so going to
+// or from token rows moves every element, not whole 16-byte units.  A tile of 2^log2_tt tokens by
+// 2^log2_wu units of the row (16 KiB) is staged in LDS as [token][row bytes of the tile]: the side that is
+// addressed by units moves 16 bytes per lane along its contiguous axis, the token-innermost side moves 16
+// bytes per lane along the tokens of one column (16/E tokens) and picks or drops them in LDS one element
+// at a time.  Both sides see only whole, aligned 16-byte accesses in global memory whenever a column's
+// piece starts on a 16-byte boundary and is wholly live; ragged ends, and pages whose columns are no
+// multiple of 16 bytes, go element by element.  Four bytes of padding per LDS row keep the walk down a
+// column from landing in one bank.
+template <int E> struct ElemType;
+template <> struct ElemType<1> { using type = uint8_t; };
+template <> struct ElemType<2> { using type = uint16_t; };
+template <> struct ElemType<4> { using type = uint32_t; };
+template <> struct ElemType<8> { using type = uint64_t; };
+
+template <int E>
+__device__ __forceinline__ typename ElemType<E>::type lds_get(const unsigned char *p) {
+    if constexpr (E == 8) { // the rows of the stage are only 4-byte aligned
+        const uint32_t *q = reinterpret_cast<const uint32_t *>(p);
+        return (uint64_t)q[0] | ((uint64_t)q[1] << 32);
+    } else {
+        return *reinterpret_cast<const typename ElemType<E>::type *>(p);
+    }
+}
+template <int E>
+__device__ __forceinline__ void lds_put(unsigned char *p, typename ElemType<E>::type v) {
+    if constexpr (E == 8) {
+        uint32_t *q = reinterpret_cast<uint32_t *>(p);
+        q[0] = (uint32_t)v;
+        q[1] = (uint32_t)(v >> 32);
+    } else {
+        *reinterpret_cast<typename ElemType<E>::type *>(p) = v;
+    }
+}
+template <int E, int NT>
+__device__ __forceinline__ typename ElemType<E>::type ld_elem(const char *p) {
+    using T = typename ElemType<E>::type;
+    if (NT != 0) return __builtin_nontemporal_load(reinterpret_cast<const T *>(p));
+    return *reinterpret_cast<const T *>(p);
+}
+template <int E, int NT>
+__device__ __forceinline__ void st_elem(char *p, typename ElemType<E>::type v) {
+    using T = typename ElemType<E>::type;
+    if (NT != 0) __builtin_nontemporal_store(v, reinterpret_cast<T *>(p));
+    else *reinterpret_cast<T *>(p) = v;
+}
+
+__device__ __forceinline__ uint64_t elem_unit_offset(const ElemSide &g, uint32_t u) {
+    const uint32_t q = g.units_per_granule == 1u ? u : __umulhi(u, g.granule_magic);
+    return (uint64_t)q * g.granule_step + (uint64_t)(u - q * g.units_per_granule) * 16u;
+}
+
+template <int E, int SK, int DK, int NT>
+__global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run *__restrict__ runs,
+                                                                  const char *__restrict__ src,
+                                                                  char *__restrict__ dst, ElemParams p) {
+    using T = typename ElemType<E>::type;
+    constexpr int kPerLane = kElemCells / kElemThreads;
+    constexpr uint32_t X = 16u / E;                 // tokens in 16 bytes of a column
+    constexpr uint32_t kLog2X = X == 16 ? 4 : (X == 8 ? 3 : (X == 4 ? 2 : 1));
+    __shared__ __align__(16) unsigned char stage[kElemCells * 16 + 4 * kElemMaxTokens];
+    union Unit {
+        u32x4 v;
+        T e[X];
+    };
+    const uint32_t width = 16u << p.log2_wu;        // bytes of the row per tile
+    const uint32_t pitch = width + 4u;
+    const uint32_t log2_gt = p.log2_tt - kLog2X;    // 16-byte pieces per column of the tile
+    const uint32_t tiles_per_run = p.tiles_t * p.tiles_w;
+
+    uint32_t first = blockIdx.x;
+    if (p.swizzle_chunk) first = (blockIdx.x & 7u) * p.swizzle_chunk + (blockIdx.x >> 3);
+
+    for (uint64_t v64 = first; v64 < p.total_tiles; v64 += gridDim.x) {
+        const uint32_t v = (uint32_t)v64;
+        const uint32_t sidx = v % tiles_per_run;
+        const uint32_t q = v / tiles_per_run;
+        uint32_t lc, e;
+        if (p.order == 2) {
+            const uint32_t i = q % p.group;
+            const uint32_t q2 = q / p.group;
+            lc = q2 % p.num_lc;
+            e = (q2 / p.num_lc) * p.group + i;
+        } else {
+            e = q % p.num_runs;
+            lc = q / p.num_runs;
+        }
+        lc += p.lc_first;
+        const kvx_run run = runs[e];
+        const uint32_t tokens = run.bytes / p.row;
+        const uint32_t t0 = (sidx / p.tiles_w) << p.log2_tt;
+        const uint32_t w0 = (sidx % p.tiles_w) << p.log2_wu; // first unit of the row in this tile
+        if (t0 >= tokens) continue; // uniform over the workgroup: no barrier is skipped by part of it
+        const uint32_t live = tokens - t0;                   // tokens of the run from the tile's first one on
+
+        const uint32_t layer = p.layer_begin + (lc >> 1);
+        const uint32_t kv = lc & 1u;
+        const uint64_t seg = (uint64_t)lc * run.seq_len * p.row;
+        const char *sp = src + run.src_off + (p.s.is_buf ? seg : layer * p.s.stride_layer + kv * p.s.stride_kv);
+        char *dp = dst + run.dst_off + (p.d.is_buf ? seg : layer * p.d.stride_layer + kv * p.d.stride_kv);
+
+        // ---- source -> stage
+        if (SK != 2) {
+            u32x4 r[kPerLane] = {};
+            bool ok[kPerLane];
+#pragma unroll
+            for (int k = 0; k < kPerLane; ++k) {
+                uint32_t t, u;
+                cell_to_tu<SK == 1>(k * kElemThreads + threadIdx.x, p.log2_tt, p.log2_wu, t, u);
+                ok[k] = t < live && w0 + u < p.units_per_row;
+                if (ok[k]) {
+                    const char *a = sp + (uint64_t)(t0 + t) * p.s.token_step + elem_unit_offset(p.s, w0 + u);
+                    r[k] = p.cached_loads ? ld16<0>(a) : ld16<NT>(a);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < kPerLane; ++k) {
+                uint32_t t, u;
+                cell_to_tu<SK == 1>(k * kElemThreads + threadIdx.x, p.log2_tt, p.log2_wu, t, u);
+                if (ok[k]) {
+                    uint32_t *w = reinterpret_cast<uint32_t *>(stage + t * pitch + u * 16u);
+                    w[0] = r[k].x; w[1] = r[k].y; w[2] = r[k].z; w[3] = r[k].w;
+                }
+            }
+        } else {
+            Unit r[kPerLane];
+            int how[kPerLane]; // 0 nothing, 1 a whole aligned piece (already loaded), 2 element by element
+#pragma unroll
+            for (int k = 0; k < kPerLane; ++k) {
+                const uint32_t c = k * kElemThreads + threadIdx.x;
+                const uint32_t ta = (c & ((1u << log2_gt) - 1u)) << kLog2X, jl = c >> log2_gt;
+                const uint32_t jb = w0 * 16u + jl * E;  // byte of the row this column starts at
+                const char *a = sp + (uint64_t)(jb / E) * p.s.column_step + (uint64_t)(t0 + ta) * E;
+                how[k] = (ta < live && jb < p.row) ? ((ta + X <= live && ((uintptr_t)a & 15u) == 0) ? 1 : 2) : 0;
+                if (how[k] == 1) r[k].v = p.cached_loads ? ld16<0>(a) : ld16<NT>(a);
+            }
+#pragma unroll
+            for (int k = 0; k < kPerLane; ++k) {
+                const uint32_t c = k * kElemThreads + threadIdx.x;
+                const uint32_t ta = (c & ((1u << log2_gt) - 1u)) << kLog2X, jl = c >> log2_gt;
+                unsigned char *w = stage + ta * pitch + jl * E;
+                if (how[k] == 1) {
+#pragma unroll
+                    for (uint32_t i = 0; i < X; ++i) lds_put<E>(w + i * pitch, r[k].e[i]);
+                } else if (how[k] == 2) {
+                    const uint32_t jb = w0 * 16u + jl * E;
+                    const char *a = sp + (uint64_t)(jb / E) * p.s.column_step + (uint64_t)(t0 + ta) * E;
+                    for (uint32_t i = 0; i < X && ta + i < live; ++i)
+                        lds_put<E>(w + i * pitch, p.cached_loads ? ld_elem<E, 0>(a + i * E) : ld_elem<E, NT>(a + i * E));
+                }
+            }
+        }
+        __syncthreads();
+        // ---- stage -> destination
+        if (DK != 2) {
+#pragma unroll
+            for (int k = 0; k < kPerLane; ++k) {
+                uint32_t t, u;
+                cell_to_tu<DK == 1>(k * kElemThreads + threadIdx.x, p.log2_tt, p.log2_wu, t, u);
+                if (t < live && w0 + u < p.units_per_row) {
+                    const uint32_t *w = reinterpret_cast<const uint32_t *>(stage + t * pitch + u * 16u);
+                    const u32x4 val = {w[0], w[1], w[2], w[3]};
+                    char *a = dp + (uint64_t)(t0 + t) * p.d.token_step + elem_unit_offset(p.d, w0 + u);
+                    if (p.cached_stores) st16<0>(a, val);
+                    else st16<NT>(a, val);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < kPerLane; ++k) {
+                const uint32_t c = k * kElemThreads + threadIdx.x;
+                const uint32_t ta = (c & ((1u << log2_gt) - 1u)) << kLog2X, jl = c >> log2_gt;
+                const uint32_t jb = w0 * 16u + jl * E;
+                if (ta >= live || jb >= p.row) continue;
+                char *a = dp + (uint64_t)(jb / E) * p.d.column_step + (uint64_t)(t0 + ta) * E;
+                const unsigned char *w = stage + ta * pitch + jl * E;
+                if (ta + X <= live && ((uintptr_t)a & 15u) == 0) {
+                    Unit val;
+#pragma unroll
+                    for (uint32_t i = 0; i < X; ++i) val.e[i] = lds_get<E>(w + i * pitch);
+                    if (p.cached_stores) st16<0>(a, val.v);
+                    else st16<NT>(a, val.v);
+                } else {
+                    for (uint32_t i = 0; i < X && ta + i < live; ++i) {
+                        if (p.cached_stores) st_elem<E, 0>(a + i * E, lds_get<E>(w + i * pitch));
+                        else st_elem<E, NT>(a + i * E, lds_get<E>(w + i * pitch));
+                    }
+                }
+            }
+        }
+        __syncthreads(); // the next tile of this workgroup reuses the stage
     }
 }
 
@@ -625,6 +844,41 @@ hipError_t launch_xpose(const XposeParams &p, bool src_token_fast, bool dst_toke
                               : xpose_sd<true, false>(p, nontemporal, grid, stream);
     return dst_token_fast ? xpose_sd<false, true>(p, nontemporal, grid, stream)
                           : xpose_sd<false, false>(p, nontemporal, grid, stream);
+}
+
+namespace {
+template <int E, int SK, int DK>
+hipError_t xpose_elem_esd(const ElemParams &p, int nt, uint32_t grid, hipStream_t stream) {
+    if (nt)
+        KVX_LAUNCH((xpose_elem_kernel<E, SK, DK, 1>), dim3(grid), dim3(kElemThreads), 0, stream, p.runs, p.src, p.dst, p);
+    else
+        KVX_LAUNCH((xpose_elem_kernel<E, SK, DK, 0>), dim3(grid), dim3(kElemThreads), 0, stream, p.runs, p.src, p.dst, p);
+    return hipGetLastError();
+}
+template <int E>
+hipError_t xpose_elem_e(const ElemParams &p, int sk, int dk, int nt, uint32_t grid, hipStream_t stream) {
+    switch (sk * 3 + dk) { // at least one side is token-innermost (kind 2)
+    case 0 * 3 + 2: return xpose_elem_esd<E, 0, 2>(p, nt, grid, stream);
+    case 1 * 3 + 2: return xpose_elem_esd<E, 1, 2>(p, nt, grid, stream);
+    case 2 * 3 + 0: return xpose_elem_esd<E, 2, 0>(p, nt, grid, stream);
+    case 2 * 3 + 1: return xpose_elem_esd<E, 2, 1>(p, nt, grid, stream);
+    case 2 * 3 + 2: return xpose_elem_esd<E, 2, 2>(p, nt, grid, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+} // namespace
+
+hipError_t launch_xpose_elem(const ElemParams &p, uint32_t elem_bytes, int src_kind, int dst_kind, int nontemporal,
+                             uint32_t grid, hipStream_t stream) {
+    if (p.total_tiles == 0 || grid == 0) return hipSuccess;
+    if (p.log2_tt < 4 || (1u << p.log2_tt) > kElemMaxTokens || p.log2_tt + p.log2_wu != 10) return hipErrorInvalidValue;
+    switch (elem_bytes) {
+    case 1: return xpose_elem_e<1>(p, src_kind, dst_kind, nontemporal, grid, stream);
+    case 2: return xpose_elem_e<2>(p, src_kind, dst_kind, nontemporal, grid, stream);
+    case 4: return xpose_elem_e<4>(p, src_kind, dst_kind, nontemporal, grid, stream);
+    case 8: return xpose_elem_e<8>(p, src_kind, dst_kind, nontemporal, grid, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_plain_copy(char *dst, const char *src, uint64_t bytes, uint32_t threads, uint32_t unroll,

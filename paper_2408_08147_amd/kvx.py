@@ -18,7 +18,7 @@ from . import build as _build
 (OK, ERR_INVALID_ARG, ERR_ALIGNMENT, ERR_BLOCK_TABLE, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_DEVICE,
  ERR_BUSY, ERR_HOST_MEMORY) = range(9)
 LAYOUT_LAYER_MAJOR, LAYOUT_PAGE_MAJOR = 0, 1
-INNER_TOKEN_ROWS, INNER_HEAD_MAJOR, INNER_DIM_SPLIT_TOKEN = 0, 1, 2
+INNER_TOKEN_ROWS, INNER_HEAD_MAJOR, INNER_DIM_SPLIT_TOKEN, INNER_TOKEN_INNERMOST = 0, 1, 2, 3
 OP_PACK, OP_UNPACK, OP_CONVERT = 0, 1, 2
 
 EXPORTS = (

@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "kvx.h"
+#include "kvx_internal.h"
 
 static uint64_t state = 0x9E3779B97F4A7C15ull;
 static uint64_t rnd() {
@@ -17,8 +18,32 @@ static uint64_t rnd() {
 }
 static uint32_t below(uint32_t n) { return n ? (uint32_t)(rnd() % n) : 0; }
 
+// The multiply-shift division the data movers use for their tile indices, against the plain quotient.
+static int check_fast_div() {
+    const uint32_t edge[] = {0u, 1u, 2u, 3u, 7u, 8u, 9u, 255u, 256u, 65535u, 65536u, 0x7FFFFFFFu, 0x80000000u,
+                             0x80000001u, 0xFFFFFFFEu, 0xFFFFFFFFu};
+    for (uint32_t d : edge) {
+        if (!d) continue;
+        const kvx::FastDiv f = kvx::make_fast_div(d);
+        for (uint32_t n : edge)
+            if (kvx::fast_div(n, f) != n / d) { printf("fast_div(%u, %u) is wrong\n", n, d); return 1; }
+    }
+    for (int i = 0; i < 2000000; ++i) {
+        uint32_t d = (uint32_t)rnd() >> below(32), n = (uint32_t)rnd() >> below(32);
+        if (!d) d = 1;
+        const kvx::FastDiv f = kvx::make_fast_div(d);
+        if (kvx::fast_div(n, f) != n / d || kvx::fast_div(n - n % d, f) != n / d ||
+            (n / d && kvx::fast_div(n - n % d - 1, f) != n / d - 1)) {
+            printf("fast_div(%u, %u) is wrong\n", n, d);
+            return 1;
+        }
+    }
+    return 0;
+}
+
 int main(int argc, char **argv) {
     const int iters = argc > 1 ? atoi(argv[1]) : 20000;
+    if (check_fast_div()) return 1;
     long ok = 0, rejected = 0;
     for (int it = 0; it < iters; ++it) {
         kvx_pool_desc s{}, d{};
@@ -30,12 +55,12 @@ int main(int argc, char **argv) {
         s.page_tokens = below(30) == 0 ? 0 : 1 + below(40);
         s.num_pages = 1 + below(300);
         s.layout = below(12) == 0 ? 5 : below(2);
-        s.inner = below(15) == 0 ? 3 : below(3);
+        s.inner = below(15) == 0 ? 4 : below(4);
         d = s;
         d.page_tokens = 1 + below(40);
         d.num_pages = 1 + below(300);
         d.layout = below(2);
-        d.inner = below(3);
+        d.inner = below(4);
         if (below(10) == 0) d.head_dim *= 2;
         if (below(10) == 0) { // explicit strides, sometimes inconsistent
             const uint64_t row = (uint64_t)s.num_kv_heads * s.head_dim * s.elem_bytes;

@@ -1,6 +1,7 @@
 """GPU parity for pools whose pages are not [token][head][dim] inside: head-major
-pages and pages with the token axis inside 16-byte groups of the head dimension,
-on either side, against the oracle, byte for byte (canaries included)."""
+pages, pages with the token axis inside 16-byte groups of the head dimension, and
+pages with the token axis innermost element by element, on either side, against
+the oracle, byte for byte (canaries included)."""
 import numpy as np
 import pytest
 
@@ -9,7 +10,7 @@ from tests import gpu_util as G
 
 pytestmark = pytest.mark.gpu
 
-ROWS, HEADS, SPLIT = 0, 1, 2
+ROWS, HEADS, SPLIT, TINNER = 0, 1, 2, 3
 LM, PM = 0, 1
 
 
@@ -24,6 +25,9 @@ def check(case, seed, ranges=None, launch=None):
 
 COMBOS = [(HEADS, ROWS), (ROWS, HEADS), (ROWS, SPLIT), (SPLIT, ROWS), (SPLIT, HEADS), (HEADS, SPLIT),
           (SPLIT, SPLIT), (HEADS, HEADS)]
+# the token axis innermost on at least one side: elements change place below the 16-byte grain
+COMBOS_TINNER = [(ROWS, TINNER), (TINNER, ROWS), (TINNER, TINNER), (HEADS, TINNER), (TINNER, HEADS),
+                 (SPLIT, TINNER), (TINNER, SPLIT)]
 
 
 @pytest.mark.parametrize("ins,ind", COMBOS)
@@ -38,6 +42,43 @@ def test_inner_arrangements(ins, ind, H, D, e, Ps, Pd, ls, ld):
     lens = [0, 1, 15, 16, 17, 200, 129, Ps, Pd, 2 * Pd + 1]
     case = G.make_case(rng, 3, H, D, e, lens, Ps, Pd, ls, ld, inner_s=ins, inner_d=ind)
     check(case, 11, ranges=[(0, 3), (1, 2)])
+
+
+@pytest.mark.parametrize("ins,ind", COMBOS_TINNER)
+@pytest.mark.parametrize("H,D,e,Ps,Pd,ls,ld", [
+    (8, 128, 2, 128, 16, LM, PM),      # 2 KiB rows, 128 -> 16 tokens per page: columns of 256 and 32 bytes
+    (1, 128, 2, 16, 16, LM, LM),       # one head: 256-byte rows
+    (3, 48, 1, 5, 7, PM, LM),          # 1-byte elements, pages of 5 and 7 tokens: no column starts aligned
+    (2, 64, 4, 64, 128, LM, LM),       # 4-byte elements
+    (1, 16, 8, 512, 40, LM, PM),       # 8-byte elements, more tokens per page than a tile holds, 40*8 = 320-byte columns
+    (2, 64, 1, 16, 48, PM, PM),        # 1-byte elements, 16 tokens = exactly one 16-byte piece per column
+])
+def test_token_innermost_arrangements(ins, ind, H, D, e, Ps, Pd, ls, ld):
+    rng = np.random.default_rng(100 + ins * 10 + ind + Ps)
+    lens = [0, 1, 15, 16, 17, 200, 129, Ps, Pd, 2 * Pd + 1, 3 * Ps + 7]
+    case = G.make_case(rng, 3, H, D, e, lens, Ps, Pd, ls, ld, inner_s=ins, inner_d=ind)
+    check(case, 17, ranges=[(0, 3), (1, 2)])
+
+
+@pytest.mark.parametrize("launch", [dict(order=1), dict(order=2), dict(xcd_swizzle=1), dict(nontemporal=1),
+                                    dict(nontemporal=2), dict(nontemporal=3), dict(max_workgroups=5),
+                                    dict(order=2, max_workgroups=16), dict(order=3)])
+def test_token_innermost_results_do_not_depend_on_launch_config(launch):
+    rng = np.random.default_rng(18)
+    case = G.make_case(rng, 2, 4, 64, 2, [300, 1, 77, 0, 64, 33], 32, 16, LM, PM, inner_s=TINNER, inner_d=TINNER)
+    check(case, 19, launch=launch)
+    case = G.make_case(rng, 2, 4, 64, 2, [300, 1, 77, 0, 64, 33], 32, 16, PM, LM, inner_s=SPLIT, inner_d=TINNER)
+    check(case, 20, launch=launch)
+
+
+def test_token_innermost_shared_pages_and_layer_triggers():
+    rng = np.random.default_rng(21)
+    case = G.make_case(rng, 4, 2, 64, 2, [100, 7, 260, 33], 16, 8, LM, PM, shared_src=True, extra=1,
+                       inner_s=TINNER, inner_d=ROWS)
+    check(case, 22, ranges=[(0, 4), (3, 4), (1, 3)])
+    case = G.make_case(rng, 4, 2, 64, 2, [100, 7, 260, 33], 24, 8, PM, LM, shared_src=True, extra=1,
+                       inner_s=ROWS, inner_d=TINNER)
+    check(case, 23, ranges=[(0, 4), (2, 3)])
 
 
 @pytest.mark.parametrize("launch", [dict(order=1), dict(order=2), dict(xcd_swizzle=1), dict(nontemporal=1),

@@ -9,10 +9,13 @@ from tests import gpu_util as G
 pytestmark = pytest.mark.gpu
 
 
-def draw_case(seed):
+def draw_case(seed, token_innermost=False):
     rng = np.random.default_rng(seed)
-    e = int(rng.choice([1, 2, 4]))
+    e = int(rng.choice([1, 2, 4, 8] if token_innermost else [1, 2, 4]))
     ins, ind = int(rng.integers(0, 3)), int(rng.integers(0, 3))
+    if token_innermost:      # on one side or on both; the other side keeps any of the four arrangements
+        which = int(rng.integers(0, 3))
+        ins, ind = (3, int(rng.integers(0, 4))) if which == 0 else ((int(rng.integers(0, 4)), 3) if which == 1 else (3, 3))
     # head_dim*e must be a multiple of 16 for the non-row arrangements, the row always
     D = int(rng.choice([16, 32, 48, 64, 128])) if (ins or ind) else int(rng.choice([8, 16, 24, 64, 128]))
     H = int(rng.integers(1, 9))
@@ -44,6 +47,15 @@ def draw_case(seed):
 @pytest.mark.parametrize("seed", range(1000, 1300))
 def test_random_case(seed):
     case, (l0, l1), launch, rng = draw_case(seed)
+    src = rng.integers(0, 256, size=case.pool_bytes(case.s), dtype=np.uint8)
+    want = G.run_oracle(case, src, l0, l1)
+    got = G.run_gpu(case, src, l0, l1, launch=launch)
+    G.assert_same(got, want, f"seed {seed} layers [{l0},{l1}) launch {launch}")
+
+
+@pytest.mark.parametrize("seed", range(2000, 2150))
+def test_random_case_with_token_innermost_pages(seed):
+    case, (l0, l1), launch, rng = draw_case(seed, token_innermost=True)
     src = rng.integers(0, 256, size=case.pool_bytes(case.s), dtype=np.uint8)
     want = G.run_oracle(case, src, l0, l1)
     got = G.run_gpu(case, src, l0, l1, launch=launch)

@@ -73,7 +73,15 @@ def test_inner_arrangement_errors():
     _, b = _simple()
     ok = kvx.pool_desc(2, 8, 128, 2, 16, 64, inner=kvx.INNER_DIM_SPLIT_TOKEN)
     kvx.kvx_plan(ok, b, ok, b, 0, 2).destroy()
-    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, kvx.pool_desc(2, 8, 128, 2, 16, 64, inner=3), b, None, None, 0, 2)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, kvx.pool_desc(2, 8, 128, 2, 16, 64, inner=4), b, None, None, 0, 2)
+    # token axis innermost: elements of 1, 2, 4 or 8 bytes, no condition on the head dimension but the row's
+    tin = kvx.pool_desc(2, 8, 128, 2, 16, 64, inner=kvx.INNER_TOKEN_INNERMOST)
+    kvx.kvx_plan(tin, b, ok, b, 0, 2).destroy()
+    kvx.kvx_plan(kvx.pool_desc(2, 4, 4, 1, 16, 64, inner=3), b, None, None, 0, 2).destroy()   # 4-byte heads, 16-byte row
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, kvx.pool_desc(2, 1, 16, 3, 16, 64, inner=3), b, None, None, 0, 2)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, kvx.pool_desc(2, 1, 16, 16, 16, 64, inner=3), b, None, None, 0, 2)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan,
+           kvx.pool_desc(2, 8, 128, 2, 16, 64, strides=(1 << 22, 1 << 21, 1 << 15, 2048), inner=3), b, None, None, 0, 2)
     strided = kvx.pool_desc(2, 8, 128, 2, 16, 64, strides=(1 << 22, 1 << 21, 1 << 15, 2048), inner=1)
     expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan, strided, b, None, None, 0, 2)
     # head_dim*elem_bytes must be a multiple of 16 even when the whole row is
