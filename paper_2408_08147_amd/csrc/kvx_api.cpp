@@ -752,15 +752,33 @@ kvx_status run_xpose_elem(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t l
     ep.lc_first = 2 * (lb - plan->l0);
     ep.num_lc = 2 * (le - lb);
     ep.num_runs = (uint32_t)o.num_runs;
-    // A tile is 16 KiB: as many tokens as a run can have (long pieces along the token axis are what the
-    // token-innermost side writes contiguously), between 16 and 256, and the rest along the row.
-    const uint32_t max_tokens = o.max_run_bytes / ep.row;
+    // A convert whose token-innermost side has the coarser pages, a whole number of the other side's: tiles
+    // span a group of runs (one coarse page), so that the pieces of its columns are as long as the page
+    // allows instead of as short as a run.  A finer side that is token-innermost too must not have a
+    // 16-byte piece straddle two of its pages.
+    uint32_t max_tokens = o.max_run_bytes / ep.row;
+    if (op == OP_CONVERT && o.group_slots > 1 && o.group_slots <= kElemMaxGroup) {
+        const uint32_t ps = gs.desc.page_tokens, pd = gd.desc.page_tokens;
+        const bool src_coarse = ps > pd;
+        const Geometry &coarse = src_coarse ? gs : gd, &fine = src_coarse ? gd : gs;
+        const uint32_t pc = coarse.desc.page_tokens, pf = fine.desc.page_tokens;
+        if (coarse.token_innermost && pc % pf == 0 && (!fine.token_innermost || (pf * elem) % 16 == 0)) {
+            ep.group_mode = src_coarse ? 1 : 2;
+            ep.num_groups = ep.num_runs / o.group_slots;
+            ep.coarse_tokens = pc;
+            ep.fine_tokens = pf;
+            ep.by_fine = make_fast_div(pf);
+            max_tokens = pc;
+        }
+    }
+    // A tile is 16 KiB: as many tokens as a run (or group) can have (long pieces along the token axis are
+    // what the token-innermost side moves contiguously), between 16 and 256, and the rest along the row.
     ep.log2_tt = 4;
     while (ep.log2_tt < 8 && (1u << ep.log2_tt) < max_tokens) ++ep.log2_tt;
     ep.log2_wu = 10 - ep.log2_tt;
     ep.tiles_t = (max_tokens + (1u << ep.log2_tt) - 1) >> ep.log2_tt;
     ep.tiles_w = (ep.units_per_row + (1u << ep.log2_wu) - 1) >> ep.log2_wu;
-    const uint64_t total = (uint64_t)ep.num_lc * ep.num_runs * ep.tiles_t * ep.tiles_w;
+    const uint64_t total = (uint64_t)ep.num_lc * (ep.group_mode ? ep.num_groups : ep.num_runs) * ep.tiles_t * ep.tiles_w;
     if (total >= (1ull << 32)) return KVX_ERR_UNSUPPORTED;
     ep.total_tiles = (uint32_t)total;
     ep.order = c.order == 3 ? 1u : c.order;
@@ -781,6 +799,7 @@ kvx_status run_xpose_elem(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t l
     // instead of piece by piece (measured on 128 <-> 16 tokens: reads 4.1 -> 5.2 TB/s, writes 1.4 -> ?).
     ep.cached_loads = (sk == 2 && (uint64_t)max_tokens * elem < 128u && max_tokens < gs.desc.page_tokens) ? 1u : 0u;
     ep.cached_stores = (dk == 2 && (uint64_t)max_tokens * elem < 128u && max_tokens < gd.desc.page_tokens) ? 1u : 0u;
+    if (ep.group_mode) ep.cached_loads = ep.cached_stores = 0; // whole pieces: nothing to share through the L2
     hipError_t e = launch_xpose_elem(ep, elem, sk, dk, nt, grid, static_cast<hipStream_t>(stream));
     return hip_ok(e, "xpose_elem_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
 }

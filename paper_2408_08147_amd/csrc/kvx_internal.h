@@ -26,6 +26,30 @@ enum Op : uint32_t { OP_PACK = 0, OP_UNPACK = 1, OP_CONVERT = 2, NUM_OPS = 3 };
 constexpr int kNumScans = 6;
 enum Scan : int { SCAN_TOKENS = 0, SCAN_PAGES_S = 1, SCAN_PAGES_D = 2, SCAN_RUNS0 = 3 };
 
+// Division of any 32-bit n by a fixed divisor d >= 1 as a multiply-high and two shifts (Granlund and
+// Montgomery's round-up method), the constants worked out once on the host: the data movers split a flat
+// tile index by several run-time divisors per tile, and the hardware has no integer divide.
+struct FastDiv {
+    uint32_t d, mul, sh1, sh2;
+};
+inline FastDiv make_fast_div(uint32_t d) {
+    FastDiv f{d ? d : 1u, 0, 0, 0};
+    uint32_t l = 0;
+    while (l < 32 && (1ull << l) < f.d) ++l;                       // l = ceil(log2 d)
+    f.mul = (uint32_t)((((1ull << l) - f.d) << 32) / f.d + 1ull);
+    f.sh1 = l < 1 ? l : 1;
+    f.sh2 = l ? l - 1 : 0;
+    return f;
+}
+__host__ __device__ inline uint32_t fast_div(uint32_t n, const FastDiv &f) {
+#ifdef __HIP_DEVICE_COMPILE__
+    const uint32_t t = __umulhi(f.mul, n);
+#else
+    const uint32_t t = (uint32_t)(((uint64_t)f.mul * n) >> 32);
+#endif
+    return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
+
 // One side of a copy as the run-building kernel sees it.  quantum == 0 means
 // the contiguous buffer (no page boundary ever breaks a run).
 struct SideGeom {
@@ -74,30 +98,6 @@ struct FillParams {
     const uint64_t *run_prefix[NUM_OPS];
     kvx_run *runs[NUM_OPS];
 };
-
-// Division of any 32-bit n by a fixed divisor d >= 1 as a multiply-high and two shifts (Granlund and
-// Montgomery's round-up method), the constants worked out once on the host: the data movers split a flat
-// tile index by several run-time divisors per tile, and the hardware has no integer divide.
-struct FastDiv {
-    uint32_t d, mul, sh1, sh2;
-};
-inline FastDiv make_fast_div(uint32_t d) {
-    FastDiv f{d ? d : 1u, 0, 0, 0};
-    uint32_t l = 0;
-    while (l < 32 && (1ull << l) < f.d) ++l;                       // l = ceil(log2 d)
-    f.mul = (uint32_t)((((1ull << l) - f.d) << 32) / f.d + 1ull);
-    f.sh1 = l < 1 ? l : 1;
-    f.sh2 = l ? l - 1 : 0;
-    return f;
-}
-__host__ __device__ inline uint32_t fast_div(uint32_t n, const FastDiv &f) {
-#ifdef __HIP_DEVICE_COMPILE__
-    const uint32_t t = __umulhi(f.mul, n);
-#else
-    const uint32_t t = (uint32_t)(((uint64_t)f.mul * n) >> 32);
-#endif
-    return (t + ((n - t) >> f.sh1)) >> f.sh2;
-}
 
 struct CopyParams {
     const kvx_run *runs;
@@ -179,11 +179,19 @@ struct ElemParams {
     uint32_t swizzle_chunk;
     uint32_t cached_loads;            // 1: loads keep the default cache policy whatever the kernel's own is
     uint32_t cached_stores;           // 1: the same for stores
+    // Tiles that span a whole group of a convert's runs (one page of the coarser side): 0 = off, 1 = the
+    // source is the coarser side, 2 = the destination is.
+    uint32_t group_mode;
+    uint32_t num_groups;              // num_runs / group
+    uint32_t coarse_tokens;           // tokens per page of the coarser side
+    uint32_t fine_tokens;             // tokens per page of the finer side (divides coarse_tokens)
+    FastDiv by_fine;
 };
 
 constexpr uint32_t kElemThreads = 256;
 constexpr uint32_t kElemCells = 1024;   // 16-byte units per tile
 constexpr uint32_t kElemMaxTokens = 256; // tokens per tile at most (rows of 64 bytes per tile at least)
+constexpr uint32_t kElemMaxGroup = 64;   // runs per group at most for tiles that span a group
 
 // elem_bytes in {1,2,4,8}; kinds as in ElemSide, at least one of them 2; nontemporal 0 or 1.
 hipError_t launch_xpose_elem(const ElemParams &p, uint32_t elem_bytes, int src_kind, int dst_kind, int nontemporal,

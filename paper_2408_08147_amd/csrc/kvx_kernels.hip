@@ -532,7 +532,13 @@ __device__ __forceinline__ uint64_t elem_unit_offset(const ElemSide &g, uint32_t
     return (uint64_t)q * g.granule_step + (uint64_t)(u - q * g.units_per_granule) * 16u;
 }
 
-template <int E, int SK, int DK, int NT>
+// GM (group mode), for a convert whose token-innermost side has the coarser pages: 0 = a tile belongs to one
+// run; 1 / 2 = a tile spans the tokens of one whole group of runs, i.e. one page of the coarser side, which is
+// the source (1) or the destination (2).  The coarser side is then addressed from the group's first record
+// (its runs follow one another inside that one page), the finer side run by run through a small table of
+// the group's offsets in LDS.  Per run, a fine receiver would hand each tile only a short piece of every
+// column of the coarse page, a fraction of a 128-byte line; per group the pieces are whole.
+template <int E, int SK, int DK, int NT, int GM>
 __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run *__restrict__ runs,
                                                                   const char *__restrict__ src,
                                                                   char *__restrict__ dst, ElemParams p) {
@@ -541,6 +547,7 @@ __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run 
     constexpr uint32_t X = 16u / E;                 // tokens in 16 bytes of a column
     constexpr uint32_t kLog2X = X == 16 ? 4 : (X == 8 ? 3 : (X == 4 ? 2 : 1));
     __shared__ __align__(16) unsigned char stage[kElemCells * 16 + 4 * kElemMaxTokens];
+    __shared__ uint64_t fine_off[GM ? kElemMaxGroup : 1];
     union Unit {
         u32x4 v;
         T e[X];
@@ -549,6 +556,7 @@ __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run 
     const uint32_t pitch = width + 4u;
     const uint32_t log2_gt = p.log2_tt - kLog2X;    // 16-byte pieces per column of the tile
     const uint32_t tiles_per_run = p.tiles_t * p.tiles_w;
+    const uint32_t num_units = GM ? p.num_groups : p.num_runs; // what the tile space counts: groups or runs
 
     uint32_t first = blockIdx.x;
     if (p.swizzle_chunk) first = (blockIdx.x & 7u) * p.swizzle_chunk + (blockIdx.x >> 3);
@@ -558,28 +566,65 @@ __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run 
         const uint32_t sidx = v % tiles_per_run;
         const uint32_t q = v / tiles_per_run;
         uint32_t lc, e;
-        if (p.order == 2) {
+        if (GM) {                       // one "run" per group: no inner group index to keep together
+            if (p.order == 2) {
+                lc = q % p.num_lc;
+                e = q / p.num_lc;
+            } else {
+                e = q % num_units;
+                lc = q / num_units;
+            }
+        } else if (p.order == 2) {
             const uint32_t i = q % p.group;
             const uint32_t q2 = q / p.group;
             lc = q2 % p.num_lc;
             e = (q2 / p.num_lc) * p.group + i;
         } else {
-            e = q % p.num_runs;
-            lc = q / p.num_runs;
+            e = q % num_units;
+            lc = q / num_units;
         }
         lc += p.lc_first;
-        const kvx_run run = runs[e];
-        const uint32_t tokens = run.bytes / p.row;
+        const kvx_run run = runs[GM ? e * p.group : e];
+        // tokens this tile space unit holds: those of the run, or those of the whole group (the group's first
+        // run starts at a page boundary of the coarser side, and the request may end inside that page)
+        const uint32_t tokens = GM ? min(p.coarse_tokens, run.seq_len - run.token) : run.bytes / p.row;
         const uint32_t t0 = (sidx / p.tiles_w) << p.log2_tt;
         const uint32_t w0 = (sidx % p.tiles_w) << p.log2_wu; // first unit of the row in this tile
-        if (t0 >= tokens) continue; // uniform over the workgroup: no barrier is skipped by part of it
-        const uint32_t live = tokens - t0;                   // tokens of the run from the tile's first one on
+        if (run.bytes == 0 || t0 >= tokens) continue; // uniform over the workgroup: no barrier is skipped by part of it
+        const uint32_t live = tokens - t0;                   // tokens from the tile's first one on
 
         const uint32_t layer = p.layer_begin + (lc >> 1);
         const uint32_t kv = lc & 1u;
         const uint64_t seg = (uint64_t)lc * run.seq_len * p.row;
-        const char *sp = src + run.src_off + (p.s.is_buf ? seg : layer * p.s.stride_layer + kv * p.s.stride_kv);
-        char *dp = dst + run.dst_off + (p.d.is_buf ? seg : layer * p.d.stride_layer + kv * p.d.stride_kv);
+        const uint64_t s_lc = p.s.is_buf ? seg : layer * p.s.stride_layer + kv * p.s.stride_kv;
+        const uint64_t d_lc = p.d.is_buf ? seg : layer * p.d.stride_layer + kv * p.d.stride_kv;
+        if (GM) {
+            if (threadIdx.x < p.group) {
+                const kvx_run *r = runs + e * p.group + threadIdx.x;
+                fine_off[threadIdx.x] = GM == 1 ? r->dst_off : r->src_off;
+            }
+            __syncthreads();
+        }
+        // Where token `t` of the tile lives on a side: the base its addressing starts from, and the token's
+        // index from there.  The finer side of a group changes base with every run.
+        auto src_at = [&](uint32_t t, uint32_t &tin) -> const char * {
+            if (GM == 2) {
+                const uint32_t i = fast_div(t0 + t, p.by_fine);
+                tin = t0 + t - i * p.fine_tokens;
+                return src + fine_off[i] + s_lc;
+            }
+            tin = t0 + t;
+            return src + run.src_off + s_lc;
+        };
+        auto dst_at = [&](uint32_t t, uint32_t &tin) -> char * {
+            if (GM == 1) {
+                const uint32_t i = fast_div(t0 + t, p.by_fine);
+                tin = t0 + t - i * p.fine_tokens;
+                return dst + fine_off[i] + d_lc;
+            }
+            tin = t0 + t;
+            return dst + run.dst_off + d_lc;
+        };
 
         // ---- source -> stage
         if (SK != 2) {
@@ -587,11 +632,12 @@ __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run 
             bool ok[kPerLane];
 #pragma unroll
             for (int k = 0; k < kPerLane; ++k) {
-                uint32_t t, u;
+                uint32_t t, u, tin;
                 cell_to_tu<SK == 1>(k * kElemThreads + threadIdx.x, p.log2_tt, p.log2_wu, t, u);
                 ok[k] = t < live && w0 + u < p.units_per_row;
                 if (ok[k]) {
-                    const char *a = sp + (uint64_t)(t0 + t) * p.s.token_step + elem_unit_offset(p.s, w0 + u);
+                    const char *a = src_at(t, tin);
+                    a += (uint64_t)tin * p.s.token_step + elem_unit_offset(p.s, w0 + u);
                     r[k] = p.cached_loads ? ld16<0>(a) : ld16<NT>(a);
                 }
             }
@@ -607,14 +653,20 @@ __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run 
         } else {
             Unit r[kPerLane];
             int how[kPerLane]; // 0 nothing, 1 a whole aligned piece (already loaded), 2 element by element
+            const char *at[kPerLane];
 #pragma unroll
             for (int k = 0; k < kPerLane; ++k) {
                 const uint32_t c = k * kElemThreads + threadIdx.x;
                 const uint32_t ta = (c & ((1u << log2_gt) - 1u)) << kLog2X, jl = c >> log2_gt;
                 const uint32_t jb = w0 * 16u + jl * E;  // byte of the row this column starts at
-                const char *a = sp + (uint64_t)(jb / E) * p.s.column_step + (uint64_t)(t0 + ta) * E;
-                how[k] = (ta < live && jb < p.row) ? ((ta + X <= live && ((uintptr_t)a & 15u) == 0) ? 1 : 2) : 0;
-                if (how[k] == 1) r[k].v = p.cached_loads ? ld16<0>(a) : ld16<NT>(a);
+                how[k] = 0;
+                if (ta < live && jb < p.row) {
+                    uint32_t tin;
+                    const char *a = src_at(ta, tin);
+                    at[k] = a += (uint64_t)(jb / E) * p.s.column_step + (uint64_t)tin * E;
+                    how[k] = (ta + X <= live && ((uintptr_t)a & 15u) == 0) ? 1 : 2;
+                    if (how[k] == 1) r[k].v = p.cached_loads ? ld16<0>(a) : ld16<NT>(a);
+                }
             }
 #pragma unroll
             for (int k = 0; k < kPerLane; ++k) {
@@ -625,10 +677,9 @@ __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run 
 #pragma unroll
                     for (uint32_t i = 0; i < X; ++i) lds_put<E>(w + i * pitch, r[k].e[i]);
                 } else if (how[k] == 2) {
-                    const uint32_t jb = w0 * 16u + jl * E;
-                    const char *a = sp + (uint64_t)(jb / E) * p.s.column_step + (uint64_t)(t0 + ta) * E;
                     for (uint32_t i = 0; i < X && ta + i < live; ++i)
-                        lds_put<E>(w + i * pitch, p.cached_loads ? ld_elem<E, 0>(a + i * E) : ld_elem<E, NT>(a + i * E));
+                        lds_put<E>(w + i * pitch,
+                                   p.cached_loads ? ld_elem<E, 0>(at[k] + i * E) : ld_elem<E, NT>(at[k] + i * E));
                 }
             }
         }
@@ -637,12 +688,13 @@ __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run 
         if (DK != 2) {
 #pragma unroll
             for (int k = 0; k < kPerLane; ++k) {
-                uint32_t t, u;
+                uint32_t t, u, tin;
                 cell_to_tu<DK == 1>(k * kElemThreads + threadIdx.x, p.log2_tt, p.log2_wu, t, u);
                 if (t < live && w0 + u < p.units_per_row) {
                     const uint32_t *w = reinterpret_cast<const uint32_t *>(stage + t * pitch + u * 16u);
                     const u32x4 val = {w[0], w[1], w[2], w[3]};
-                    char *a = dp + (uint64_t)(t0 + t) * p.d.token_step + elem_unit_offset(p.d, w0 + u);
+                    char *a = dst_at(t, tin);
+                    a += (uint64_t)tin * p.d.token_step + elem_unit_offset(p.d, w0 + u);
                     if (p.cached_stores) st16<0>(a, val);
                     else st16<NT>(a, val);
                 }
@@ -654,7 +706,9 @@ __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run 
                 const uint32_t ta = (c & ((1u << log2_gt) - 1u)) << kLog2X, jl = c >> log2_gt;
                 const uint32_t jb = w0 * 16u + jl * E;
                 if (ta >= live || jb >= p.row) continue;
-                char *a = dp + (uint64_t)(jb / E) * p.d.column_step + (uint64_t)(t0 + ta) * E;
+                uint32_t tin;
+                char *a = dst_at(ta, tin);
+                a += (uint64_t)(jb / E) * p.d.column_step + (uint64_t)tin * E;
                 const unsigned char *w = stage + ta * pitch + jl * E;
                 if (ta + X <= live && ((uintptr_t)a & 15u) == 0) {
                     Unit val;
@@ -670,7 +724,7 @@ __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run 
                 }
             }
         }
-        __syncthreads(); // the next tile of this workgroup reuses the stage
+        __syncthreads(); // the next tile of this workgroup reuses the stage (and the table of offsets)
     }
 }
 
@@ -847,13 +901,21 @@ hipError_t launch_xpose(const XposeParams &p, bool src_token_fast, bool dst_toke
 }
 
 namespace {
+template <int E, int SK, int DK, int GM>
+hipError_t xpose_elem_esdg(const ElemParams &p, int nt, uint32_t grid, hipStream_t stream) {
+    if (nt)
+        KVX_LAUNCH((xpose_elem_kernel<E, SK, DK, 1, GM>), dim3(grid), dim3(kElemThreads), 0, stream, p.runs, p.src, p.dst, p);
+    else
+        KVX_LAUNCH((xpose_elem_kernel<E, SK, DK, 0, GM>), dim3(grid), dim3(kElemThreads), 0, stream, p.runs, p.src, p.dst, p);
+    return hipGetLastError();
+}
 template <int E, int SK, int DK>
 hipError_t xpose_elem_esd(const ElemParams &p, int nt, uint32_t grid, hipStream_t stream) {
-    if (nt)
-        KVX_LAUNCH((xpose_elem_kernel<E, SK, DK, 1>), dim3(grid), dim3(kElemThreads), 0, stream, p.runs, p.src, p.dst, p);
-    else
-        KVX_LAUNCH((xpose_elem_kernel<E, SK, DK, 0>), dim3(grid), dim3(kElemThreads), 0, stream, p.runs, p.src, p.dst, p);
-    return hipGetLastError();
+    // a group's tile is addressed from the coarser side, which is the token-innermost one (kind 2)
+    if (SK == 2 && p.group_mode == 1) return xpose_elem_esdg<E, SK, DK, (SK == 2 ? 1 : 0)>(p, nt, grid, stream);
+    if (DK == 2 && p.group_mode == 2) return xpose_elem_esdg<E, SK, DK, (DK == 2 ? 2 : 0)>(p, nt, grid, stream);
+    if (p.group_mode) return hipErrorInvalidValue;
+    return xpose_elem_esdg<E, SK, DK, 0>(p, nt, grid, stream);
 }
 template <int E>
 hipError_t xpose_elem_e(const ElemParams &p, int sk, int dk, int nt, uint32_t grid, hipStream_t stream) {
@@ -872,6 +934,7 @@ hipError_t launch_xpose_elem(const ElemParams &p, uint32_t elem_bytes, int src_k
                              uint32_t grid, hipStream_t stream) {
     if (p.total_tiles == 0 || grid == 0) return hipSuccess;
     if (p.log2_tt < 4 || (1u << p.log2_tt) > kElemMaxTokens || p.log2_tt + p.log2_wu != 10) return hipErrorInvalidValue;
+    if (p.group_mode && (p.group == 0 || p.group > kElemMaxGroup || p.fine_tokens == 0)) return hipErrorInvalidValue;
     switch (elem_bytes) {
     case 1: return xpose_elem_e<1>(p, src_kind, dst_kind, nontemporal, grid, stream);
     case 2: return xpose_elem_e<2>(p, src_kind, dst_kind, nontemporal, grid, stream);

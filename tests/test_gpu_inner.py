@@ -52,6 +52,9 @@ def test_inner_arrangements(ins, ind, H, D, e, Ps, Pd, ls, ld):
     (2, 64, 4, 64, 128, LM, LM),       # 4-byte elements
     (1, 16, 8, 512, 40, LM, PM),       # 8-byte elements, more tokens per page than a tile holds, 40*8 = 320-byte columns
     (2, 64, 1, 16, 48, PM, PM),        # 1-byte elements, 16 tokens = exactly one 16-byte piece per column
+    (2, 32, 1, 256, 2, LM, LM),        # 128 runs per coarse page: more than a tile spanning the page can take
+    (2, 32, 1, 64, 8, LM, PM),         # fine pages of 8 one-byte tokens: half a 16-byte piece per column
+    (1, 64, 2, 24, 8, PM, LM),         # three fine pages per coarse one
 ])
 def test_token_innermost_arrangements(ins, ind, H, D, e, Ps, Pd, ls, ld):
     rng = np.random.default_rng(100 + ins * 10 + ind + Ps)
