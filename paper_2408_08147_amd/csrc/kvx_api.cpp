@@ -369,12 +369,13 @@ namespace {
 // tile (256 lanes x 16 B) with the largest grid is fastest; with the run group outermost (page-major
 // receiver) one workgroup per whole run, up to 512 lanes x 4 x 16 B = 32 KiB, is.
 // Cache policy when the caller left it open (values as in kvx_launch_cfg, minus one for the kernels).
-// Measured on MI355X: agent-scope stores gain 1-2 % where long runs are written into a pool and on a plain
-// copy, and lose 3-8 % where the runs are short or the writes go to the buffer; non-temporal loads and
-// stores are the safe choice everywhere else.
-int resolve_policy(uint32_t nontemporal, bool writes_pool, uint32_t max_run_bytes) {
+// Measured on MI355X: agent-scope stores gain 1-2 % wherever the runs are long (128 KiB and more), into a
+// pool or into the buffer alike, and on a plain copy; they lose up to 8 % where the runs are short.
+// Non-temporal loads and stores are the safe choice there.  `flat_copy`: the kernel for [token][head][dim]
+// pages; the tile kernels gather a run's bytes in pieces, so for a pack they keep the non-temporal stores.
+int resolve_policy(uint32_t nontemporal, bool flat_copy, bool writes_pool, uint32_t max_run_bytes) {
     if (nontemporal) return (int)nontemporal - 1;
-    return (writes_pool && max_run_bytes >= 128u * 1024u) ? 2 : 1;
+    return ((writes_pool || flat_copy) && max_run_bytes >= 128u * 1024u) ? 2 : 1;
 }
 
 void resolve_tile(uint32_t order, uint32_t max_run_bytes, uint32_t *threads, uint32_t *unroll) {
@@ -707,7 +708,7 @@ kvx_status run_xpose(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, co
         grid = (grid + 7u) / 8u * 8u;
         xp.swizzle_chunk = grid / 8u;
     }
-    hipError_t e = launch_xpose(xp, src_tf, dst_tf, resolve_policy(c.nontemporal, op != OP_PACK, o.max_run_bytes), grid,
+    hipError_t e = launch_xpose(xp, src_tf, dst_tf, resolve_policy(c.nontemporal, false, op != OP_PACK, o.max_run_bytes), grid,
                                 static_cast<hipStream_t>(stream));
     return hip_ok(e, "xpose_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
 }
@@ -889,7 +890,7 @@ kvx_status kvx::run_op(const kvx_plan_s *plan, Op op, uint32_t lb, uint32_t le, 
     // small tiles of the other orders have anyway) is 3 % faster.  Unless the caller chose a tile or a cap.
     uint32_t per_cu = c.workgroups_per_cu;
     if (!per_cu && cp.order == 2 && !c.threads && !c.unroll) per_cu = std::max(1u, 32768u / tile);
-    hipError_t e = launch_copy(cp, threads, unroll, resolve_policy(c.nontemporal, op != OP_PACK, o.max_run_bytes), grid,
+    hipError_t e = launch_copy(cp, threads, unroll, resolve_policy(c.nontemporal, true, op != OP_PACK, o.max_run_bytes), grid,
                                occupancy_lds(per_cu),
                                static_cast<hipStream_t>(stream));
     return hip_ok(e, "copy_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
