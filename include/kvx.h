@@ -44,9 +44,9 @@
  *   - A pool addresses a row as
  *         layer*stride_layer + kv*stride_kv + page*stride_page + slot*stride_token
  *     with kv = 0 for K, 1 for V.  (Pools whose pages are not [token][head][dim]
- *     inside, see kvx_inner, address 16-byte units instead of rows; they are
- *     moved by a kernel that stages tiles through LDS where the two sides
- *     disagree on which axis is contiguous.)
+ *     inside, see kvx_inner, address 16-byte units or single elements instead
+ *     of rows; they are moved by kernels that stage tiles through LDS where the
+ *     two sides disagree on which axis is contiguous.)
  *   - The buffer of a plan over layers [l0,l1) holds the requests in batch order
  *     with no padding; inside a request the layers ascend, each layer is all K
  *     rows then all V rows, tokens ascending ("one after another").  With
@@ -351,7 +351,8 @@ kvx_status kvx_retriever_acquire(kvx_retriever_t *ret, uint64_t ticket, uint64_t
  * in the slot's workspace and enqueues kvx_unpack, both on the slot's stream,
  * behind whatever the caller enqueued there.  `launch` may be NULL; a capped
  * grid (max_workgroups) keeps most of the device for the running batch.  On an
- * error the slot stays acquired; release it with kvx_retriever_abandon. */
+ * error the slot stays acquired (release it with kvx_retriever_abandon); after a
+ * KVX_ERR_DEVICE the contents of the slot's workspace are undefined. */
 kvx_status kvx_retriever_scatter(kvx_retriever_t *ret, uint32_t slot, const kvx_pool_desc *d,
                                  const kvx_batch_desc *db, uint32_t layer_begin, uint32_t layer_end,
                                  void *dst_pool, const kvx_launch_cfg *launch);

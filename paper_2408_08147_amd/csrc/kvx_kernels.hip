@@ -487,8 +487,10 @@ __global__ __launch_bounds__(kXposeThreads) void xpose_kernel(const kvx_run *__r
 // bytes per lane along the tokens of one column (16/E tokens) and picks or drops them in LDS one element
 // at a time.  Both sides see only whole, aligned 16-byte accesses in global memory whenever a column's
 // piece starts on a 16-byte boundary and is wholly live; ragged ends, and pages whose columns are no
-// multiple of 16 bytes, go element by element.  Four bytes of padding per LDS row keep the walk down a
-// column from landing in one bank.
+// multiple of 16 bytes, go element by element.  In LDS, row t starts 4 bytes after a multiple of the tile's
+// width and is rotated by 8 bytes per group of 16/E tokens: a wave that walks down the columns (16 or more
+// groups of tokens, a few neighbouring columns) then touches every bank once instead of four of them
+// sixteen times.
 template <int E> struct ElemType;
 template <> struct ElemType<1> { using type = uint8_t; };
 template <> struct ElemType<2> { using type = uint16_t; };
@@ -555,6 +557,10 @@ __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run 
     const uint32_t width = 16u << p.log2_wu;        // bytes of the row per tile
     const uint32_t pitch = width + 4u;
     const uint32_t log2_gt = p.log2_tt - kLog2X;    // 16-byte pieces per column of the tile
+    // byte `b` of the tile's row of token `t` in the stage (b and the rotation are multiples of the access size)
+    auto at_stage = [&](uint32_t t, uint32_t b) -> uint32_t {
+        return t * pitch + ((b + ((t >> kLog2X) << 3)) & (width - 1u));
+    };
     const uint32_t tiles_per_run = p.tiles_t * p.tiles_w;
     const uint32_t num_units = GM ? p.num_groups : p.num_runs; // what the tile space counts: groups or runs
 
@@ -646,8 +652,10 @@ __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run 
                 uint32_t t, u;
                 cell_to_tu<SK == 1>(k * kElemThreads + threadIdx.x, p.log2_tt, p.log2_wu, t, u);
                 if (ok[k]) {
-                    uint32_t *w = reinterpret_cast<uint32_t *>(stage + t * pitch + u * 16u);
-                    w[0] = r[k].x; w[1] = r[k].y; w[2] = r[k].z; w[3] = r[k].w;
+                    const uint32_t d[4] = {r[k].x, r[k].y, r[k].z, r[k].w};
+#pragma unroll
+                    for (uint32_t i = 0; i < 4; ++i) // dword by dword: the rotation may wrap inside a unit
+                        *reinterpret_cast<uint32_t *>(stage + at_stage(t, u * 16u + 4u * i)) = d[i];
                 }
             }
         } else {
@@ -672,14 +680,14 @@ __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run 
             for (int k = 0; k < kPerLane; ++k) {
                 const uint32_t c = k * kElemThreads + threadIdx.x;
                 const uint32_t ta = (c & ((1u << log2_gt) - 1u)) << kLog2X, jl = c >> log2_gt;
-                unsigned char *w = stage + ta * pitch + jl * E;
+                unsigned char *w = stage + at_stage(ta, jl * E); // one group of tokens: the same rotation for all
                 if (how[k] == 1) {
 #pragma unroll
                     for (uint32_t i = 0; i < X; ++i) lds_put<E>(w + i * pitch, r[k].e[i]);
                 } else if (how[k] == 2) {
-                    for (uint32_t i = 0; i < X && ta + i < live; ++i)
-                        lds_put<E>(w + i * pitch,
-                                   p.cached_loads ? ld_elem<E, 0>(at[k] + i * E) : ld_elem<E, NT>(at[k] + i * E));
+                    // a ragged piece comes element by element out of one or two 64-byte sectors: loads that
+                    // may stay in the cache, so that the sector is fetched once
+                    for (uint32_t i = 0; i < X && ta + i < live; ++i) lds_put<E>(w + i * pitch, ld_elem<E, 0>(at[k] + i * E));
                 }
             }
         }
@@ -691,8 +699,11 @@ __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run 
                 uint32_t t, u, tin;
                 cell_to_tu<DK == 1>(k * kElemThreads + threadIdx.x, p.log2_tt, p.log2_wu, t, u);
                 if (t < live && w0 + u < p.units_per_row) {
-                    const uint32_t *w = reinterpret_cast<const uint32_t *>(stage + t * pitch + u * 16u);
-                    const u32x4 val = {w[0], w[1], w[2], w[3]};
+                    uint32_t d[4];
+#pragma unroll
+                    for (uint32_t i = 0; i < 4; ++i)
+                        d[i] = *reinterpret_cast<const uint32_t *>(stage + at_stage(t, u * 16u + 4u * i));
+                    const u32x4 val = {d[0], d[1], d[2], d[3]};
                     char *a = dst_at(t, tin);
                     a += (uint64_t)tin * p.d.token_step + elem_unit_offset(p.d, w0 + u);
                     if (p.cached_stores) st16<0>(a, val);
@@ -709,7 +720,7 @@ __global__ __launch_bounds__(kElemThreads) void xpose_elem_kernel(const kvx_run 
                 uint32_t tin;
                 char *a = dst_at(ta, tin);
                 a += (uint64_t)(jb / E) * p.d.column_step + (uint64_t)tin * E;
-                const unsigned char *w = stage + ta * pitch + jl * E;
+                const unsigned char *w = stage + at_stage(ta, jl * E);
                 if (ta + X <= live && ((uintptr_t)a & 15u) == 0) {
                     Unit val;
 #pragma unroll
