@@ -303,6 +303,40 @@ def test_plan_reuse_and_immediate_destroy():
         assert np.array_equal(dst.cpu().numpy(), want.dst_unpack)
 
 
+def test_pinned_staging_blocks_are_reused_and_released_on_request():
+    """Tables too large for a launch's arguments are staged in pinned blocks the library keeps between plans:
+    plans made back to back (nothing completes in between) each get their own, idle ones are handed out
+    again, kvx_release_cached gives them all back, and a plan made afterwards still comes out right."""
+    import torch
+    rng = np.random.default_rng(12)
+    lens = rng.integers(1, 40, size=700).astype(np.uint32)          # 700 + 2 x ~1100 words: beyond 896
+    case = G.make_case(rng, 1, 1, 16, 1, lens, 16, 16)
+    src = rng.integers(0, 256, size=case.pool_bytes(case.s), dtype=np.uint8)
+    want = G.run_oracle(case, src, 0, 1)
+    dev = torch.device("cuda:0")
+    st = torch.cuda.Stream(device=dev)
+    sp, dp = case.kvx_pool(case.s), case.kvx_pool(case.d)
+    sb = kvx.BatchDesc(case.seq_lens, case.ids_s, case.offs_s)
+    db = kvx.BatchDesc(case.seq_lens, case.ids_d, case.offs_d)
+    nws = kvx.kvx_plan_workspace_bytes(sp, sb, dp, db)
+    torch.cuda.synchronize()
+    kvx.kvx_release_cached()                                          # whatever earlier tests left behind
+    assert kvx.kvx_release_cached() == 0
+    with torch.cuda.stream(st):
+        src_t = torch.from_numpy(src).to(dev)
+        wss = [torch.empty(nws, dtype=torch.uint8, device=dev) for _ in range(5)]
+        for ws in wss:
+            kvx.kvx_plan(sp, sb, dp, db, 0, 1, ws.data_ptr(), nws, st.cuda_stream).destroy()
+    st.synchronize()
+    freed = kvx.kvx_release_cached()
+    assert 0 < freed <= 5 * 64 * 1024 and freed % 4096 == 0, freed
+    assert kvx.kvx_release_cached() == 0
+    got = G.run_gpu(case, src, 0, 1)
+    G.assert_same(got, want, "after the release")
+    torch.cuda.synchronize()
+    assert kvx.kvx_release_cached() > 0
+
+
 def test_runtime_argument_errors():
     import torch
     rng = np.random.default_rng(10)
