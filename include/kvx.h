@@ -390,7 +390,10 @@ kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const 
  *     plan's device tables <= KVX_NOALLOC_SCRATCH_BYTES: beyond either, KVX_ERR_CAPACITY and nothing is
  *     enqueued;
  *   - default launch configuration.
- * Three kernel launches on `stream` (scan, fill, unpack).  Every call on a GPU uses that GPU's one
+ * Three kernel launches on `stream` (scan, fill, unpack) and nothing else, so the call may be recorded while
+ * `stream` is being captured into a HIP graph; the first call on a device also asks the runtime for the
+ * scratch array's address (and, for a page-major receiver, raises a kernel's LDS limit once), so make one
+ * call on the device before capturing.  Every call on a GPU uses that GPU's one
  * scratch array: it keeps the previous call's tables, each call rewrites everything it reads, and calls
  * on the same stream are ordered; calls that overlap on one GPU (different streams, or threads on
  * different streams) race on the array and must be serialised by the caller. */

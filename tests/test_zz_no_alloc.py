@@ -72,3 +72,54 @@ def test_limits_are_errors_and_nothing_is_written():
     assert e.value.status == kvx.ERR_CAPACITY
     torch.cuda.synchronize()
     assert bool((dst == G.CANARY_POOL).all())
+
+
+def test_under_graph_capture_and_replay():
+    """The caller this entry point is for: the whole RecvScatter (plan kernels and unpack) recorded into a HIP
+    graph and replayed, with eager work and new bytes between the replays, against kvx_plan + kvx_unpack run
+    eagerly on the same bytes.  The first call on a device looks the scratch array's address up, so one call
+    is made before the capture begins."""
+    import torch
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(79)
+    L, H, D, e, P = 3, 8, 128, 2, 16
+    lens = np.array([300, 17, 0, 1024, 48], dtype=np.uint32)
+    used = int(sum((int(n) + P - 1) // P for n in lens))
+    num_pages = 2 * used + 3
+    ids, offs = G.tables(rng, lens, P, num_pages, unique=True)
+    d = kvx.pool_desc(L, H, D, e, P, num_pages, 1)
+    db = kvx.BatchDesc(lens, ids, offs)
+    row = H * D * e
+    total = L * 2 * row * int(lens.sum())
+    pool_bytes = L * 2 * num_pages * P * row
+    st = torch.cuda.Stream(device=dev)
+    with torch.cuda.stream(st):
+        buf = torch.zeros(total, dtype=torch.uint8, device=dev)
+        got = torch.full((pool_bytes,), G.CANARY_POOL, dtype=torch.uint8, device=dev)
+        want = torch.full((pool_bytes,), G.CANARY_POOL, dtype=torch.uint8, device=dev)
+        nws = kvx.kvx_plan_workspace_bytes(None, None, d, db)
+        ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+        plan = kvx.kvx_plan(None, None, d, db, 0, L, ws.data_ptr(), nws, st.cuda_stream)
+        kvx.kvx_unpack_noalloc(d, db, 0, L, buf.data_ptr(), total, got.data_ptr(), st.cuda_stream)   # outside the graph
+    st.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=st):
+        kvx.kvx_unpack_noalloc(d, db, 0, L, buf.data_ptr(), total, got.data_ptr(), st.cuda_stream)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        buf.copy_(torch.from_numpy(rng.integers(0, 256, size=total, dtype=np.uint8)))
+        got.fill_(G.CANARY_POOL)
+        want.fill_(G.CANARY_POOL)
+        # another call in between leaves other tables in the scratch array; the replay must rewrite all it reads
+        other = kvx.BatchDesc([5], [1], [0, 1])
+        kvx.kvx_unpack_noalloc(d, other, 0, 1, buf.data_ptr(), total, want.data_ptr(), 0)
+        torch.cuda.synchronize()
+        want.fill_(G.CANARY_POOL)
+        torch.cuda.synchronize()
+        graph.replay()
+        with torch.cuda.stream(st):
+            kvx.kvx_unpack(plan, buf.data_ptr(), total, want.data_ptr(), st.cuda_stream)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), f"replay {rep}: {int((got != want).sum())} bytes differ"
+        assert bool((got != G.CANARY_POOL).any())
+    plan.destroy()
