@@ -265,7 +265,10 @@ def measure(workload: int, K: int, Wm: int, with_cpu: bool):
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_launch": 2 * s.payload,
-                     "traffic": traffic, "traffic_from": traffic_from},
+                     "traffic": traffic, "traffic_from": traffic_from,
+                     # beside the published peak: what a plain contiguous copy of the same access shape
+                     # reached in this very process (kvx_copy_yardstick)
+                     "frac_of_plain_copy": round(achieved / (2 * half / yard_ms / 1e6), 4)},
     }
     if with_cpu:
         out["cpu_baseline"] = cpu_baseline(s, convert_only)
