@@ -201,7 +201,8 @@ kvx_status kvx_plan_workspace_bytes(const kvx_pool_desc *s, const kvx_batch_desc
  * go into the workspace (inside the next kernel's launch arguments when they
  * are at most 896 words together, else staged in pinned memory and copied),
  * a wavefront prefix-scan kernel over the variable lengths, and a kernel that
- * writes the kvx_run records.  The plan may be used on `stream` right away,
+ * writes the kvx_run records (one kernel does both when the tables ride in
+ * its launch arguments).  The plan may be used on `stream` right away,
  * and on other streams after `stream` has been synchronised with them.
  *
  * With a sender side the plan serves kvx_pack, with a receiver side
@@ -390,7 +391,7 @@ kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const 
  *     plan's device tables <= KVX_NOALLOC_SCRATCH_BYTES: beyond either, KVX_ERR_CAPACITY and nothing is
  *     enqueued;
  *   - default launch configuration.
- * Three kernel launches on `stream` (scan, fill, unpack) and nothing else, so the call may be recorded while
+ * Two kernel launches on `stream` (the planner, then the unpack) and nothing else, so the call may be recorded while
  * `stream` is being captured into a HIP graph; the first call on a device also asks the runtime for the
  * scratch array's address (and, for a page-major receiver, raises a kernel's LDS limit once), so make one
  * call on the device before capturing.  Every call on a GPU uses that GPU's one

@@ -412,6 +412,7 @@ void kvx::planner_params(const kvx_plan_s &p, ScanParams *scan, FillParams *fill
         src_side.stride_token = p.s.token_step;
         src_side.page_tokens = p.s.desc.page_tokens;
         src_side.quantum = p.s.quantum;
+        src_side.which = 1;
     }
     if (p.d.present) {
         dst_side.ids = reinterpret_cast<const uint32_t *>(p.ws + z.off_ids_d);
@@ -420,6 +421,7 @@ void kvx::planner_params(const kvx_plan_s &p, ScanParams *scan, FillParams *fill
         dst_side.stride_token = p.d.token_step;
         dst_side.page_tokens = p.d.desc.page_tokens;
         dst_side.quantum = p.d.quantum;
+        dst_side.which = 2;
     }
     fp.src[OP_PACK] = src_side;   fp.dst[OP_PACK] = buf_side;
     fp.src[OP_UNPACK] = buf_side; fp.dst[OP_UNPACK] = dst_side;
@@ -558,12 +560,14 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
         ScanParams sp{};
         FillParams fp{};
         planner_params(*p, &sp, &fp);
-        if (tables_inline)
-            ok = ok && hip_ok(launch_scan_inline(sp, it, reinterpret_cast<uint32_t *>(p->ws), hs),
-                              "scan_inline_kernel launch");
-        else
+        if (tables_inline) {
+            // one launch for the whole plan: a single workgroup scans and writes the runs
+            ok = ok && hip_ok(launch_plan_small(sp, fp, it, reinterpret_cast<uint32_t *>(p->ws), hs),
+                              "plan_small_kernel launch");
+        } else {
             ok = ok && hip_ok(launch_scan(sp, hs), "scan_kernel launch");
-        ok = ok && hip_ok(launch_fill(fp, hs), "fill_kernel launch");
+            ok = ok && hip_ok(launch_fill(fp, hs), "fill_kernel launch");
+        }
         if (!ok) {
             pinned_release(p->staging);
             return KVX_ERR_DEVICE;

@@ -59,6 +59,8 @@ struct SideGeom {
     uint64_t stride_token;
     uint32_t page_tokens;
     uint32_t quantum;            // tokens that are contiguous: page_tokens, 1 (padded rows) or 0 (buffer)
+    uint32_t which;              // 0 the buffer, 1 the sender's pool, 2 the receiver's
+    uint32_t pad;
 };
 
 struct ScanParams {
@@ -73,11 +75,11 @@ struct ScanParams {
     uint64_t *prefix[kNumScans]; // outputs
 };
 
-// Small batches hand their tables (lengths, then the sender's used page ids, then the receiver's) to the scan
-// kernel inside its arguments: the launch itself carries them to the device, so there is no host-to-device
-// copy to issue, no staging block to keep alive and no event to record.  The kernel stores the three
-// segments at dst_word[] (32-bit words from the start of the workspace) for the kernels that follow.
-constexpr uint32_t kInlineWords = 896; // with ScanParams this stays under the 4 KiB a launch may carry
+// Small batches hand their tables (lengths, then the sender's used page ids, then the receiver's) to the
+// planning kernel inside its arguments: the launch itself carries them to the device, so there is no
+// host-to-device copy to issue, no staging block to keep alive and no event to record.  The kernel stores the
+// three segments at dst_word[] (32-bit words from the start of the workspace), where inspection finds them.
+constexpr uint32_t kInlineWords = 896; // with the planner's own parameters this stays under the 4 KiB a launch may carry
 struct InlineTables {
     uint32_t count[3];
     uint32_t dst_word[3];
@@ -208,9 +210,10 @@ inline bool valid_threads(uint32_t t) { return t == 64 || t == 128 || t == 256 |
 inline bool valid_unroll(uint32_t u) { return u == 1 || u == 2 || u == 4 || u == 8; }
 
 hipError_t launch_scan(const ScanParams &p, hipStream_t stream);
-hipError_t launch_scan_inline(const ScanParams &p, const InlineTables &t, uint32_t *workspace_words,
-                              hipStream_t stream);
 hipError_t launch_fill(const FillParams &p, hipStream_t stream);
+// Scan and fill of a batch whose tables ride in the launch arguments, in one launch of one workgroup.
+hipError_t launch_plan_small(const ScanParams &sp, const FillParams &fp, const InlineTables &t,
+                             uint32_t *workspace_words, hipStream_t stream);
 hipError_t launch_copy(const CopyParams &p, uint32_t threads, uint32_t unroll, int nontemporal, uint32_t grid,
                        uint32_t lds_bytes, hipStream_t stream);
 

@@ -2,7 +2,7 @@
 //
 //   scan_kernel  exclusive prefix sums over the variable request lengths
 //                (tokens, pages per side, copy runs per operation), done with
-//                wavefront-level shuffles and one LDS hop across the waves of
+//                wavefront-level sums and one LDS hop across the waves of
 //                a single workgroup.  These are the offsets section 3.6 of the
 //                paper derives from prompt length, hidden size and precision.
 //   fill_kernel  writes the flat copy plan: one kvx_run per maximal span of
@@ -11,6 +11,8 @@
 //                convert the runs are laid out in groups of a fixed number of
 //                slots, one group per page of the coarser side, so that the
 //                data mover can keep a group together.
+//   plan_small_kernel  scan and fill in one launch of one workgroup, for a
+//                batch whose lengths and block tables fit the launch arguments.
 //   copy_kernel  the pack / unpack / convert data mover for pages that are
 //                [token][head][dim] with rows back to back (a run is then one
 //                flat byte range on both sides): every workgroup takes tiles
@@ -94,8 +96,9 @@ __device__ __forceinline__ uint64_t read_lane(uint64_t x, int lane) { // lane is
 }
 
 // `length_of(r)` reads request r's length: from the workspace, or straight from the launch arguments.
-template <typename Lengths>
-__device__ __forceinline__ void scan_body(const ScanParams &p, Lengths length_of) {
+// `keep(k, r, value)` sees every prefix sum as it is written (the fused planner keeps them in LDS).
+template <typename Lengths, typename Keep>
+__device__ __forceinline__ void scan_body(const ScanParams &p, Lengths length_of, Keep keep) {
     __shared__ uint64_t wave_tot[kNumScans][kScanWaves];
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63u;
@@ -137,7 +140,11 @@ __device__ __forceinline__ void scan_body(const ScanParams &p, Lengths length_of
             const uint64_t x = row_inclusive_sum(t);
             const uint64_t before = read_lane(x - t, my_wave);
             const uint64_t all = read_lane(x, kScanWaves - 1);
-            if (r < p.num_requests) p.prefix[k][r] = carry[k] + before + inc[k] - v[k];
+            if (r < p.num_requests) {
+                const uint64_t ex = carry[k] + before + inc[k] - v[k];
+                p.prefix[k][r] = ex;
+                keep(k, r, ex);
+            }
             carry[k] += all;
         }
         __syncthreads(); // the next pass overwrites the wave totals
@@ -148,48 +155,89 @@ __device__ __forceinline__ void scan_body(const ScanParams &p, Lengths length_of
 #pragma unroll
         for (int k = 0; k < kNumScans; ++k) total = (int)tid == k ? carry[k] : total;
         p.prefix[tid][p.num_requests] = total;
+        keep((int)tid, p.num_requests, total);
     }
 }
 
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanParams p) {
-    scan_body(p, [&](uint32_t r) { return p.seq_lens[r]; });
-}
-
-// The same scan for a batch whose tables arrive in the launch arguments; it first puts them where the
-// kernels after it expect them.  (The lengths are read from the arguments, not back from memory.)
-__global__ __launch_bounds__(kScanThreads) void scan_inline_kernel(ScanParams p, InlineTables t,
-                                                                   uint32_t *__restrict__ workspace_words) {
-    const uint32_t c0 = t.count[0], c01 = c0 + t.count[1], total = c01 + t.count[2];
-    constexpr int kPerLane = 4; // reads of the arguments in flight per lane before the first store
-    for (uint32_t base = 0; base < total; base += blockDim.x * kPerLane) {
-        uint32_t w[kPerLane];
-#pragma unroll
-        for (int k = 0; k < kPerLane; ++k) {
-            const uint32_t i = base + k * blockDim.x + threadIdx.x;
-            if (i < total) w[k] = t.words[i];
-        }
-#pragma unroll
-        for (int k = 0; k < kPerLane; ++k) {
-            const uint32_t i = base + k * blockDim.x + threadIdx.x;
-            if (i >= total) continue;
-            const uint32_t seg = i < c0 ? 0u : (i < c01 ? 1u : 2u);
-            const uint32_t j = i - (seg == 0u ? 0u : (seg == 1u ? c0 : c01));
-            workspace_words[t.dst_word[seg] + j] = w[k];
-        }
-    }
-    scan_body(p, [&](uint32_t r) { return t.words[r]; });
+    scan_body(p, [&](uint32_t r) { return p.seq_lens[r]; }, [](int, uint32_t, uint64_t) {});
 }
 
 // ---------------------------------------------------------------------------
 // fill
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ uint64_t side_offset(const SideGeom &g, uint32_t r, uint32_t x,
+// Where the run-building code reads its inputs: the workspace in global memory (the scan kernel wrote them
+// there), or, in the fused planner, LDS and the launch arguments.
+struct FillFromWorkspace {
+    const FillParams &p;
+    __device__ uint32_t len(uint32_t r) const { return p.seq_lens[r]; }
+    __device__ uint64_t token_prefix(uint32_t r) const { return p.token_prefix[r]; }
+    __device__ uint64_t run_prefix(uint32_t op, uint32_t r) const { return p.run_prefix[op][r]; }
+    __device__ uint64_t page(const SideGeom &g, uint32_t r, uint32_t logical) const {
+        return g.ids[g.page_prefix[r] + logical];
+    }
+};
+
+template <typename In>
+__device__ __forceinline__ uint64_t side_offset(const SideGeom &g, const In &in, uint32_t r, uint32_t x,
                                                 uint64_t buf_base, uint32_t row) {
     if (g.quantum == 0) return buf_base + (uint64_t)x * row;
     const uint32_t logical = x / g.page_tokens;
     const uint32_t slot = x - logical * g.page_tokens;
-    const uint64_t page = g.ids[g.page_prefix[r] + logical];
-    return page * g.stride_page + slot * g.stride_token;
+    return in.page(g, r, logical) * g.stride_page + slot * g.stride_token;
+}
+
+// The runs of request r for operation op, written by `nlanes` lanes of which this is lane `lane`.  `between`
+// is what separates clearing a request's convert slots from claiming them (a barrier over those lanes).
+template <typename In, typename Between>
+__device__ __forceinline__ void fill_request(const FillParams &p, const In &in, uint32_t op, uint32_t r,
+                                             uint32_t lane, uint32_t nlanes, Between between) {
+    const SideGeom &a = p.src[op];
+    const SideGeom &b = p.dst[op];
+    const uint32_t l = clamp_lcm(p.lcm[op]);
+    const uint32_t n = in.len(r);
+    if (n == 0) return; // the same for every lane that works on r
+    const uint64_t ca = ceil_div_q(n, a.quantum);
+    const uint64_t cb = ceil_div_q(n, b.quantum);
+    const uint64_t buf_base = in.token_prefix(r) * p.bytes_per_token;
+    kvx_run *out = p.runs[op] + in.run_prefix(op, r);
+    const bool grouped = (op == OP_CONVERT);
+    if (grouped) {
+        // slots that no run claims must read as empty (bytes == 0)
+        const uint64_t slots = in.run_prefix(op, r + 1) - in.run_prefix(op, r);
+        kvx_run none{};
+        for (uint64_t i = lane; i < slots; i += nlanes) out[i] = none;
+        between();
+    }
+    // one lane per cut point: the ca multiples of a's quantum, then the cb multiples of b's (all below n)
+    for (uint64_t i = lane; i < ca + cb; i += nlanes) {
+        uint32_t x;
+        if (i < ca) {
+            x = (uint32_t)i * a.quantum; // quantum 0 -> ca == 1 -> x == 0
+        } else {
+            x = (uint32_t)(i - ca) * b.quantum;
+            const bool also_a = a.quantum ? (x % a.quantum == 0) : (x == 0);
+            if (also_a) continue; // that boundary belongs to the other side's lane
+        }
+        uint64_t rank = cuts_below(x, a.quantum, b.quantum, l);
+        if (grouped) {
+            // position = group * slots + rank among the boundaries inside the group
+            const uint32_t g = x / p.group_quantum;
+            const uint32_t g0 = g * p.group_quantum;
+            rank = (uint64_t)g * p.group_slots + rank - cuts_below(g0, a.quantum, b.quantum, l);
+        }
+        uint64_t end = n;
+        if (a.quantum) end = min(end, (uint64_t)(x / a.quantum + 1u) * a.quantum);
+        if (b.quantum) end = min(end, (uint64_t)(x / b.quantum + 1u) * b.quantum);
+        kvx_run run;
+        run.src_off = side_offset(a, in, r, x, buf_base, p.row);
+        run.dst_off = side_offset(b, in, r, x, buf_base, p.row);
+        run.bytes = (uint32_t)((end - x) * p.row);
+        run.seq_len = n;
+        run.request = r;
+        run.token = x;
+        out[rank] = run;
+    }
 }
 
 constexpr int kFillThreads = 256;
@@ -198,53 +246,100 @@ constexpr int kFillThreads = 256;
 __global__ __launch_bounds__(kFillThreads) void fill_kernel(FillParams p) {
     const uint32_t op = blockIdx.y;
     if (!p.planned[op]) return;
-    const SideGeom &a = p.src[op];
-    const SideGeom &b = p.dst[op];
-    const uint32_t l = clamp_lcm(p.lcm[op]);
-    for (uint32_t r = blockIdx.x; r < p.num_requests; r += gridDim.x) {
-        const uint32_t n = p.seq_lens[r];
-        if (n == 0) continue;
-        const uint64_t ca = ceil_div_q(n, a.quantum);
-        const uint64_t cb = ceil_div_q(n, b.quantum);
-        const uint64_t buf_base = p.token_prefix[r] * p.bytes_per_token;
-        kvx_run *out = p.runs[op] + p.run_prefix[op][r];
-        const bool grouped = (op == OP_CONVERT);
-        if (grouped) {
-            // slots that no run claims must read as empty (bytes == 0)
-            const uint64_t slots = p.run_prefix[op][r + 1] - p.run_prefix[op][r];
-            kvx_run none{};
-            for (uint64_t i = threadIdx.x; i < slots; i += kFillThreads) out[i] = none;
-            __syncthreads();
-        }
-        // one thread per cut point: the ca multiples of a's quantum, then the cb multiples of b's (all below n)
-        for (uint64_t i = threadIdx.x; i < ca + cb; i += kFillThreads) {
-            uint32_t x;
-            if (i < ca) {
-                x = (uint32_t)i * a.quantum; // quantum 0 -> ca == 1 -> x == 0
-            } else {
-                x = (uint32_t)(i - ca) * b.quantum;
-                const bool also_a = a.quantum ? (x % a.quantum == 0) : (x == 0);
-                if (also_a) continue; // that boundary belongs to the other side's thread
-            }
-            uint64_t rank = cuts_below(x, a.quantum, b.quantum, l);
-            if (grouped) {
-                // position = group * slots + rank among the boundaries inside the group
-                const uint32_t g = x / p.group_quantum;
-                const uint32_t g0 = g * p.group_quantum;
-                rank = (uint64_t)g * p.group_slots + rank - cuts_below(g0, a.quantum, b.quantum, l);
-            }
-            uint64_t end = n;
-            if (a.quantum) end = min(end, (uint64_t)(x / a.quantum + 1u) * a.quantum);
-            if (b.quantum) end = min(end, (uint64_t)(x / b.quantum + 1u) * b.quantum);
-            kvx_run run;
-            run.src_off = side_offset(a, r, x, buf_base, p.row);
-            run.dst_off = side_offset(b, r, x, buf_base, p.row);
-            run.bytes = (uint32_t)((end - x) * p.row);
-            run.seq_len = n;
-            run.request = r;
-            run.token = x;
-            out[rank] = run;
-        }
+    const FillFromWorkspace in{p};
+    for (uint32_t r = blockIdx.x; r < p.num_requests; r += gridDim.x)
+        fill_request(p, in, op, r, threadIdx.x, kFillThreads, [] { __syncthreads(); });
+}
+
+// The whole plan of a small batch in one launch: one workgroup stores the tables that came in the launch
+// arguments, scans, and writes the runs, the prefix sums going from the scan to the run-building code through
+// LDS (nothing a lane wrote to global memory is read back by another inside this kernel).  A wave takes a
+// (request, operation) pair at a time.
+template <int MAXR>
+struct FillFromLds {
+    const uint32_t *words;                       // the launch's tables, copied to LDS
+    const uint64_t (*prefix)[MAXR + 1];          // [kNumScans][R+1] in LDS
+    uint32_t first_id[3];                        // where a side's page ids start in `words` (index = SideGeom::which)
+    __device__ uint32_t len(uint32_t r) const { return words[r]; }
+    __device__ uint64_t token_prefix(uint32_t r) const { return prefix[SCAN_TOKENS][r]; }
+    __device__ uint64_t run_prefix(uint32_t op, uint32_t r) const { return prefix[SCAN_RUNS0 + op][r]; }
+    __device__ uint64_t page(const SideGeom &g, uint32_t r, uint32_t logical) const {
+        const uint64_t at = prefix[g.which == 1 ? SCAN_PAGES_S : SCAN_PAGES_D][r] + logical;
+        return words[first_id[g.which] + (uint32_t)at];
+    }
+};
+
+// What the fused planner needs beyond the scan's own parameters; everything else of FillParams follows from
+// the two (a launch carries at most 4 KiB of arguments, and the tables take most of that).
+struct PlanSmallExtra {
+    SideGeom sender, receiver;
+    kvx_run *runs[NUM_OPS];
+    uint64_t bytes_per_token;
+    uint32_t row;
+    uint32_t pad;
+};
+static_assert(sizeof(ScanParams) + sizeof(PlanSmallExtra) + sizeof(InlineTables) + sizeof(void *) <= 4096,
+              "the fused planner's arguments must fit one launch");
+
+// THREADS lanes for batches of at most MAXR requests: a batch of a few requests (one request arriving at a
+// receive slot) gets a single wave and a few KiB of LDS, which finds a place on a device that is busy copying
+// far sooner than sixteen waves and their LDS on one compute unit do.
+template <int THREADS, int MAXR>
+__global__ __launch_bounds__(THREADS) void plan_small_kernel(ScanParams sp, PlanSmallExtra x, InlineTables t,
+                                                             uint32_t *__restrict__ workspace_words) {
+    __shared__ uint64_t prefix[kNumScans][MAXR + 1];
+    __shared__ uint32_t words[kInlineWords];
+    FillParams fp{};
+    fp.num_requests = sp.num_requests;
+    fp.row = x.row;
+    fp.bytes_per_token = x.bytes_per_token;
+    fp.src[OP_PACK] = x.sender;    // the buffer side of pack and unpack stays all zero
+    fp.dst[OP_UNPACK] = x.receiver;
+    fp.src[OP_CONVERT] = x.sender;
+    fp.dst[OP_CONVERT] = x.receiver;
+    fp.group_quantum = sp.group_quantum;
+    fp.group_slots = sp.group_slots;
+#pragma unroll
+    for (int op = 0; op < (int)NUM_OPS; ++op) {
+        fp.lcm[op] = sp.lcm[op];
+        fp.planned[op] = sp.planned[op];
+        fp.runs[op] = x.runs[op];
+    }
+    const uint32_t c0 = t.count[0], c01 = c0 + t.count[1], total = c01 + t.count[2];
+    // The launch arguments live in host memory: every read of them is a trip over the bus.  So they are read
+    // once, all of a lane's words in flight together, into LDS (what the scan and the run-building code read)
+    // and into the workspace (where inspection finds them).
+    constexpr int kPerLane = (kInlineWords + THREADS - 1) / THREADS;
+    uint32_t mine[kPerLane];
+#pragma unroll
+    for (int k = 0; k < kPerLane; ++k) {
+        const uint32_t i = k * THREADS + threadIdx.x;
+        if (i < total) mine[k] = t.words[i];
+    }
+#pragma unroll
+    for (int k = 0; k < kPerLane; ++k) {
+        const uint32_t i = k * THREADS + threadIdx.x;
+        if (i >= total) continue;
+        const uint32_t seg = i < c0 ? 0u : (i < c01 ? 1u : 2u);
+        const uint32_t j = i - (seg == 0u ? 0u : (seg == 1u ? c0 : c01));
+        words[i] = mine[k];
+        workspace_words[t.dst_word[seg] + j] = mine[k];
+    }
+    __syncthreads();
+    scan_body(sp, [&](uint32_t r) { return words[r]; },
+              [&](int k, uint32_t r, uint64_t v) { prefix[k][r] = v; });
+    __syncthreads();
+    const FillFromLds<MAXR> in{words, prefix, {0u, c0, c01}};
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+    // The operations one after another (unrolled: the parameters of each are then picked at compile time and
+    // stay in registers), the requests of each dealt to the waves; the waves start at different requests per
+    // operation so that a batch of one or two requests still spreads over three waves.
+#pragma unroll
+    for (int op = 0; op < (int)NUM_OPS; ++op) {
+        if (!fp.planned[op]) continue;
+        for (uint32_t r = (wave + waves - (uint32_t)op % waves) % waves; r < sp.num_requests; r += waves)
+            // one wave clears and then claims the slots: its stores to one address keep their order
+            fill_request(fp, in, (uint32_t)op, r, lane, 64u, [] { __builtin_amdgcn_wave_barrier(); });
     }
 }
 
@@ -787,14 +882,29 @@ hipError_t launch_scan(const ScanParams &p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-hipError_t launch_scan_inline(const ScanParams &p, const InlineTables &t, uint32_t *workspace_words,
-                              hipStream_t stream) {
-    // waves for the requests, and up to four of them so that one round of reads moves all the words
-    const uint32_t words = t.count[0] + t.count[1] + t.count[2];
-    const uint32_t for_requests = std::max<uint32_t>(64u, (p.num_requests + 63u) / 64u * 64u);
-    const uint32_t for_words = std::min<uint32_t>(256u, (words / 4u + 63u) / 64u * 64u);
-    const uint32_t threads = std::min<uint32_t>(kScanThreads, std::max(for_requests, for_words));
-    KVX_LAUNCH(scan_inline_kernel, dim3(1), dim3(threads), 0, stream, p, t, workspace_words);
+hipError_t launch_plan_small(const ScanParams &sp, const FillParams &fp, const InlineTables &t,
+                             uint32_t *workspace_words, hipStream_t stream) {
+    if (sp.num_requests > kInlineWords) return hipErrorInvalidValue; // the prefix sums would not fit the LDS arrays
+    PlanSmallExtra x{};
+    x.sender = fp.src[OP_CONVERT].which == 1 ? fp.src[OP_CONVERT] : fp.src[OP_PACK];
+    x.receiver = fp.dst[OP_CONVERT].which == 2 ? fp.dst[OP_CONVERT] : fp.dst[OP_UNPACK];
+    for (int op = 0; op < (int)NUM_OPS; ++op) x.runs[op] = fp.runs[op];
+    x.bytes_per_token = fp.bytes_per_token;
+    x.row = fp.row;
+    // A wave builds the runs of one request of one operation at a time: one wave for up to 4 requests, four
+    // while that leaves a wave at most two turns, sixteen beyond.
+    uint32_t ops = 0;
+    for (int op = 0; op < (int)NUM_OPS; ++op) ops += sp.planned[op] ? 1u : 0u;
+    if (sp.num_requests <= 4)
+        KVX_LAUNCH((plan_small_kernel<64, 4>), dim3(1), dim3(64), 0, stream, sp, x, t, workspace_words);
+    else if (sp.num_requests <= 64 && sp.num_requests * ops <= 8)
+        KVX_LAUNCH((plan_small_kernel<256, 64>), dim3(1), dim3(256), 0, stream, sp, x, t, workspace_words);
+    else if (sp.num_requests <= 64)
+        KVX_LAUNCH((plan_small_kernel<kScanThreads, 64>), dim3(1), dim3(kScanThreads), 0, stream, sp, x, t,
+                   workspace_words);
+    else
+        KVX_LAUNCH((plan_small_kernel<kScanThreads, (int)kInlineWords>), dim3(1), dim3(kScanThreads), 0, stream, sp, x, t,
+                   workspace_words);
     return hipGetLastError();
 }
 

@@ -112,10 +112,9 @@ extern "C" kvx_status kvx_unpack_noalloc(const kvx_pool_desc *d, const kvx_batch
     FillParams fp{};
     planner_params(plan, &sp, &fp);
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    // Every table the fill and unpack kernels read is rewritten by these two launches, so whatever the
-    // previous call left in the array does not matter and nothing has to be cleared first.
-    if (!hip_ok(launch_scan_inline(sp, it, reinterpret_cast<uint32_t *>(ws), hs), "scan_inline_kernel launch") ||
-        !hip_ok(launch_fill(fp, hs), "fill_kernel launch"))
+    // Every table the unpack kernel reads is rewritten by this launch, so whatever the previous call left
+    // in the array does not matter and nothing has to be cleared first.
+    if (!hip_ok(launch_plan_small(sp, fp, it, reinterpret_cast<uint32_t *>(ws), hs), "plan_small_kernel launch"))
         return KVX_ERR_DEVICE;
     return run_op(&plan, OP_UNPACK, layer_begin, layer_end, buf, dst_pool, stream);
 }

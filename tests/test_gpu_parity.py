@@ -204,7 +204,7 @@ def test_tables_on_either_side_of_the_launch_argument_limit(pages_second):
 
 
 ONE_SIDED = {
-    # tables in the scan kernel's launch arguments
+    # tables in the plan kernel's launch arguments
     "one_request": [16 * 20 - 7],
     "four_requests": [100, 0, 33, 16],
     "sixty_five_requests": [9] * 65,
