@@ -142,8 +142,8 @@ typedef struct {
     uint32_t nontemporal;   /* cache policy of the 16-byte accesses: 0 = chosen per operation, 1 = default,
                                2 = non-temporal loads and stores, 3 = non-temporal loads with agent-scope
                                (write-through) stores */
-    uint32_t order;         /* 0 = chosen per operation (pack: 3; unpack and convert: 2 into a page-major
-                               receiver, else 1), 1 = (layer,kv) outermost, 2 = copy run (for convert: group of
+    uint32_t order;         /* 0 = chosen per operation (pack: 3, with fewer than 64 runs 1; unpack and convert: 2
+                               into a page-major receiver, else 1), 1 = (layer,kv) outermost, 2 = copy run (for convert: group of
                                runs) outermost, 3 = the runs cut into eight parts, one per XCD, each part walked
                                with (layer,kv) outermost ([token][head][dim] pages only, else as 1) */
     uint32_t xcd_swizzle;   /* 1 = off, 2 = give each of the 8 XCDs contiguous tiles: one eighth of the grid
@@ -219,8 +219,17 @@ kvx_status kvx_plan_workspace_bytes(const kvx_pool_desc *s, const kvx_batch_desc
  * stride_page >= (page_tokens-1)*stride_token + row when it is the next larger,
  * and so on in order of size), else KVX_ERR_INVALID_ARG.  A sender may overlap
  * itself (it is only read).  dev_workspace == NULL with workspace_bytes == 0 builds a
- * host-only plan: no HIP call is made; totals and segments can be queried but
- * pack / unpack / convert return KVX_ERR_INVALID_ARG.
+ * host-only plan: no HIP call is made and nothing is enqueued; totals and
+ * segments can be queried.  A host-only plan can also run when it is small and
+ * simple: exactly one side given, that side's pages KVX_INNER_TOKEN_ROWS with
+ * the rows of a page back to back (stride_token equal to the row, as in every
+ * dense pool), at most KVX_INLINE_RUNS used pages (sum of ceil(seq_len/page_tokens)) and at
+ * least one.  The host then works the kvx_run records out itself (a run of a
+ * one-sided plan is the part of a request inside one page) and kvx_pack /
+ * kvx_unpack and their _layers forms carry them in their launch arguments:
+ * one launch per operation, none for the plan.  kvx_plan_can_launch tells
+ * which kind a plan is; every other host-only plan makes pack / unpack /
+ * convert return KVX_ERR_INVALID_ARG.
  *
  * KVX_ERR_UNSUPPORTED: page_tokens*row >= 2^32, or more than 2^32-1 tiles. */
 kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb,
@@ -254,7 +263,11 @@ kvx_status kvx_plan_request_segment(const kvx_plan_t *plan, uint32_t request,
                                     uint64_t *offset, uint64_t *length);
 
 /* No passage of the paper: inspection and tuning.  get_tables needs a plan with a device workspace;
- * set_launch refuses values outside the ranges kvx_launch_cfg states (KVX_ERR_INVALID_ARG). */
+ * set_launch refuses values outside the ranges kvx_launch_cfg states (KVX_ERR_INVALID_ARG);
+ * can_launch sets *out to 1 for a plan with a device workspace or with run records that ride in the
+ * launch arguments (see kvx_plan), to 0 for a plan that only answers the size queries. */
+#define KVX_INLINE_RUNS 96u
+kvx_status kvx_plan_can_launch(const kvx_plan_t *plan, int *out);
 kvx_status kvx_plan_get_tables(const kvx_plan_t *plan, kvx_plan_tables *out);
 kvx_status kvx_plan_set_launch(kvx_plan_t *plan, const kvx_launch_cfg *cfg);
 kvx_status kvx_plan_get_launch(const kvx_plan_t *plan, kvx_launch_cfg *out);
@@ -263,8 +276,8 @@ kvx_status kvx_plan_get_launch(const kvx_plan_t *plan, kvx_launch_cfg *out);
  * "Challenge", says block-free transfer has to pay): the K and V rows of every layer of every request
  * of the plan, gathered out of the sender's discrete blocks and laid one after another.
  * src_pool [device] -> buf [device].  Writes exactly the first kvx_plan_total_bytes bytes of buf;
- * buf_bytes smaller than that is KVX_ERR_CAPACITY.  Needs a plan built with a sender side and a
- * device workspace (else KVX_ERR_INVALID_ARG); pointers must be 16-byte aligned (KVX_ERR_ALIGNMENT).
+ * buf_bytes smaller than that is KVX_ERR_CAPACITY.  Needs a plan built with a sender side that
+ * kvx_plan_can_launch (else KVX_ERR_INVALID_ARG); pointers must be 16-byte aligned (KVX_ERR_ALIGNMENT).
  * One kernel launch on `stream`; neither pointer is kept. */
 kvx_status kvx_pack(const kvx_plan_t *plan, const void *src_pool, void *buf, uint64_t buf_bytes,
                     void *stream);
@@ -273,7 +286,7 @@ kvx_status kvx_pack(const kvx_plan_t *plan, const void *src_pool, void *buf, uin
  * receiver's discrete blocks restored from the received bytes.  buf [device] -> dst_pool [device].
  * Reads the first kvx_plan_total_bytes bytes of buf (buf_bytes smaller: KVX_ERR_CAPACITY) and writes
  * only the live slots of the pages the receiver's block tables list.  Needs a plan built with a
- * receiver side and a device workspace.  One kernel launch on `stream`. */
+ * receiver side that kvx_plan_can_launch.  One kernel launch on `stream`. */
 kvx_status kvx_unpack(const kvx_plan_t *plan, const void *buf, uint64_t buf_bytes, void *dst_pool,
                       void *stream);
 
@@ -350,7 +363,9 @@ kvx_status kvx_retriever_acquire(kvx_retriever_t *ret, uint64_t ticket, uint64_t
 /* RecvScatter of the slot's buffer into dst_pool [device] for the receiver's
  * geometry `d`, batch `db` and layers [layer_begin, layer_end): builds the plan
  * in the slot's workspace and enqueues kvx_unpack, both on the slot's stream,
- * behind whatever the caller enqueued there.  `launch` may be NULL; a capped
+ * behind whatever the caller enqueued there (an arrival of at most
+ * KVX_INLINE_RUNS used pages whose pages hold token rows is planned on the
+ * host instead, and the kvx_unpack is then the only launch).  `launch` may be NULL; a capped
  * grid (max_workgroups) keeps most of the device for the running batch.  On an
  * error the slot stays acquired (release it with kvx_retriever_abandon); after a
  * KVX_ERR_DEVICE the contents of the slot's workspace are undefined. */

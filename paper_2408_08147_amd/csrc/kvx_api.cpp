@@ -373,8 +373,17 @@ namespace {
 // pool or into the buffer alike, and on a plain copy; they lose up to 8 % where the runs are short.
 // Non-temporal loads and stores are the safe choice there.  `flat_copy`: the kernel for [token][head][dim]
 // pages; the tile kernels gather a run's bytes in pieces, so for a pack they keep the non-temporal stores.
-int resolve_policy(uint32_t nontemporal, bool flat_copy, bool writes_pool, uint32_t max_run_bytes) {
+// One more case takes the agent-scope stores: a pack of at most kSmallPackBytes.  What it writes is read
+// again at once (by the network, here by the unpack that stands in for it), and written through it is where
+// that reader finds it when the kernel ends, instead of waiting in the L2 for the write-back at the kernel's
+// end.  Measured with short runs (16 KiB) through the receive slots: a request (22 MB) at a time 18-21 ->
+// 15.5-19 us per request, 355 MB at a time 15.9 -> 14.5, 1.4 GB 16.3 -> 14.8, 5.7 GB no difference; a
+// 23 GB pack + unpack loses 3.6 % with them.
+constexpr uint64_t kSmallPackBytes = 2ull << 30;
+int resolve_policy(uint32_t nontemporal, bool flat_copy, bool writes_pool, uint32_t max_run_bytes,
+                   uint64_t launch_bytes) {
     if (nontemporal) return (int)nontemporal - 1;
+    if (flat_copy && !writes_pool && launch_bytes <= kSmallPackBytes) return 2;
     return ((writes_pool || flat_copy) && max_run_bytes >= 128u * 1024u) ? 2 : 1;
 }
 
@@ -572,6 +581,35 @@ kvx_status kvx_plan(const kvx_pool_desc *s, const kvx_batch_desc *sb, const kvx_
             pinned_release(p->staging);
             return KVX_ERR_DEVICE;
         }
+    } else if (s == nullptr || d == nullptr) {
+        // No workspace: a plan for the size and segment queries.  It can still run when it is small and
+        // simple enough for its run records to ride in the copy kernel's launch arguments: one side, pages
+        // that hold token rows, at most kInlineRuns used pages.  A run of a one-sided plan is the part of a
+        // request inside one page, so the records follow from the block table directly.
+        const Geometry &g = s ? p->s : p->d;
+        const Op op = s ? OP_PACK : OP_UNPACK;
+        const std::vector<uint32_t> &ids = s ? ids_s : ids_d;
+        if (g.dense_rows && !g.token_innermost && z.ops[op].num_runs > 0 && z.ops[op].num_runs <= kInlineRuns &&
+            z.ops[op].num_runs == ids.size()) {
+            p->inline_runs.reset(new InlineRuns());
+            const uint32_t P = g.desc.page_tokens;
+            size_t at = 0;
+            for (uint32_t r = 0; r < R; ++r) {
+                const uint32_t n = p->seq_lens[r];
+                for (uint32_t x = 0; x < n; x += P, ++at) {
+                    kvx_run &run = p->inline_runs->run[at];
+                    const uint64_t in_pool = (uint64_t)ids[at] * g.sp;
+                    const uint64_t in_buf = p->token_prefix[r] * p->bpt + (uint64_t)x * p->row;
+                    run.src_off = s ? in_pool : in_buf;
+                    run.dst_off = s ? in_buf : in_pool;
+                    run.bytes = (uint32_t)(std::min<uint64_t>(n - x, P) * p->row);
+                    run.seq_len = n;
+                    run.request = r;
+                    run.token = x;
+                    if (n - x <= P) { ++at; break; } // also keeps x += P from wrapping near 2^32
+                }
+            }
+        }
     }
     *out_plan = owner.release();
     return KVX_OK;
@@ -631,6 +669,12 @@ kvx_status kvx_plan_get_tables(const kvx_plan_t *plan, kvx_plan_tables *out) {
         out->runs_off[op] = plan->z.off_runs[op];
         out->num_runs[op] = plan->z.ops[op].planned ? plan->z.ops[op].num_runs : 0;
     }
+    return KVX_OK;
+}
+
+kvx_status kvx_plan_can_launch(const kvx_plan_t *plan, int *out) {
+    if (!plan || !out) return KVX_ERR_INVALID_ARG;
+    *out = (plan->ws || plan->inline_runs) ? 1 : 0;
     return KVX_OK;
 }
 
@@ -712,7 +756,7 @@ kvx_status run_xpose(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, co
         grid = (grid + 7u) / 8u * 8u;
         xp.swizzle_chunk = grid / 8u;
     }
-    hipError_t e = launch_xpose(xp, src_tf, dst_tf, resolve_policy(c.nontemporal, false, op != OP_PACK, o.max_run_bytes), grid,
+    hipError_t e = launch_xpose(xp, src_tf, dst_tf, resolve_policy(c.nontemporal, false, op != OP_PACK, o.max_run_bytes, 0), grid,
                                 static_cast<hipStream_t>(stream));
     return hip_ok(e, "xpose_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
 }
@@ -816,7 +860,7 @@ kvx_status run_xpose_elem(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t l
 kvx_status kvx::run_op(const kvx_plan_s *plan, Op op, uint32_t lb, uint32_t le, const void *src, void *dst,
                        void *stream) {
     const OpShape &o = plan->z.ops[op];
-    if (!plan->ws || !o.planned) return KVX_ERR_INVALID_ARG;
+    if ((!plan->ws && !plan->inline_runs) || !o.planned) return KVX_ERR_INVALID_ARG;
     if (lb > le || lb < plan->l0 || le > plan->l1) return KVX_ERR_INVALID_ARG;
     if (plan->total == 0 || lb == le) return KVX_OK;
     if (!src || !dst) return KVX_ERR_INVALID_ARG;
@@ -833,7 +877,7 @@ kvx_status kvx::run_op(const kvx_plan_s *plan, Op op, uint32_t lb, uint32_t le, 
         return run_xpose_elem(plan, op, lb, le, src, dst, stream);
     if (!src_rows || !dst_rows) return run_xpose(plan, op, lb, le, src, dst, stream);
     CopyParams cp{};
-    cp.runs = reinterpret_cast<const kvx_run *>(plan->ws + plan->z.off_runs[op]);
+    cp.runs = plan->ws ? reinterpret_cast<const kvx_run *>(plan->ws + plan->z.off_runs[op]) : nullptr;
     cp.src = static_cast<const char *>(src);
     cp.dst = static_cast<char *>(dst);
     cp.src_is_buf = (op == OP_UNPACK);
@@ -854,10 +898,14 @@ kvx_status kvx::run_op(const kvx_plan_s *plan, Op op, uint32_t lb, uint32_t le, 
     // (layer,kv), so that the eight XCDs gather from different pages at any moment (never slower than an
     // eighth of the (layer,kv) range each, up to 8 % faster); for unpack and convert the latter, which is
     // the faster one there.
+    // Eight parts want runs to deal out: below kRunsForParts of them the parts come out uneven (17 runs make
+    // parts of 3, 3, 3, 3, 3, 2, 0, 0), and a pack of so few is faster with (layer,kv) outermost (a request at
+    // a time through the receive slots: 19.3 -> 18.6 us per request).
+    constexpr uint64_t kRunsForParts = 64;
     cp.order = c.order;
     if (!cp.order) {
         if (op != OP_PACK && !plan->d.custom_strides && plan->d.desc.layout == KVX_LAYOUT_PAGE_MAJOR) cp.order = 2;
-        else cp.order = op == OP_PACK ? 3 : 1;
+        else cp.order = (op == OP_PACK && o.num_runs >= kRunsForParts) ? 3 : 1;
     }
     cp.group = o.group_slots;
     uint32_t threads = c.threads, unroll = c.unroll;
@@ -894,9 +942,12 @@ kvx_status kvx::run_op(const kvx_plan_s *plan, Op op, uint32_t lb, uint32_t le, 
     // small tiles of the other orders have anyway) is 3 % faster.  Unless the caller chose a tile or a cap.
     uint32_t per_cu = c.workgroups_per_cu;
     if (!per_cu && cp.order == 2 && !c.threads && !c.unroll) per_cu = std::max(1u, 32768u / tile);
-    hipError_t e = launch_copy(cp, threads, unroll, resolve_policy(c.nontemporal, true, op != OP_PACK, o.max_run_bytes), grid,
-                               occupancy_lds(per_cu),
-                               static_cast<hipStream_t>(stream));
+    const uint64_t launch_bytes = plan->total / (plan->l1 - plan->l0) * (le - lb);
+    // with a workspace the table in it is what the kernel reads, as kvx_plan_get_tables promises
+    const InlineRuns *inline_runs = plan->ws ? nullptr : plan->inline_runs.get();
+    hipError_t e = launch_copy(cp, inline_runs, threads, unroll,
+                               resolve_policy(c.nontemporal, true, op != OP_PACK, o.max_run_bytes, launch_bytes), grid,
+                               occupancy_lds(per_cu), static_cast<hipStream_t>(stream));
     return hip_ok(e, "copy_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
 }
 

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <memory>
 #include <vector>
 
 #include "kvx.h"
@@ -99,6 +100,13 @@ struct FillParams {
     uint32_t group_slots;
     const uint64_t *run_prefix[NUM_OPS];
     kvx_run *runs[NUM_OPS];
+};
+
+// Run records that ride in a copy kernel's launch arguments: what a one-sided plan of at most this many
+// used pages needs, worked out on the host, so that nothing has to be planned on the device.
+constexpr uint32_t kInlineRuns = KVX_INLINE_RUNS;
+struct InlineRuns {
+    kvx_run run[kInlineRuns];
 };
 
 struct CopyParams {
@@ -214,8 +222,9 @@ hipError_t launch_fill(const FillParams &p, hipStream_t stream);
 // Scan and fill of a batch whose tables ride in the launch arguments, in one launch of one workgroup.
 hipError_t launch_plan_small(const ScanParams &sp, const FillParams &fp, const InlineTables &t,
                              uint32_t *workspace_words, hipStream_t stream);
-hipError_t launch_copy(const CopyParams &p, uint32_t threads, uint32_t unroll, int nontemporal, uint32_t grid,
-                       uint32_t lds_bytes, hipStream_t stream);
+// `inline_runs`: nullptr to read the records at p.runs, else the records themselves (p.runs is then unused).
+hipError_t launch_copy(const CopyParams &p, const InlineRuns *inline_runs, uint32_t threads, uint32_t unroll,
+                       int nontemporal, uint32_t grid, uint32_t lds_bytes, hipStream_t stream);
 
 // LDS per compute unit on gfx950, and the unused dynamic LDS to reserve per workgroup so that at most
 // `per_cu` workgroups are resident on a compute unit (0 = no cap).
@@ -300,6 +309,7 @@ struct kvx_plan_s {
     std::vector<uint32_t> ids_s;        // sender's used page ids, request by request (for the block-by-block baseline)
     kvx::Sizing z;
     char *ws = nullptr; // device workspace (caller's), nullptr for a host-only plan
+    std::unique_ptr<kvx::InlineRuns> inline_runs; // host-only plan of a small one-sided batch: its run records
     kvx::PinnedBlock staging;
     kvx_launch_cfg launch{};
 };

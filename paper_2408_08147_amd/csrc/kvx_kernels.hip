@@ -389,9 +389,20 @@ __device__ __forceinline__ kvx_run load_run(const kvx_run *p) {
     return r;
 }
 
-template <int T, int U, int NT>
-__global__ __launch_bounds__(T) void copy_kernel(const kvx_run *__restrict__ runs, const char *__restrict__ src,
-                                                 char *__restrict__ dst, CopyParams p) {
+// Where a workgroup finds run record e: in the plan's table in device memory, or among the records that
+// ride in the launch arguments (a small one-sided batch whose runs the host worked out).
+struct RunsInMemory {
+    const kvx_run *__restrict__ runs;
+    __device__ __forceinline__ kvx_run at(uint32_t e) const { return load_run(runs + e); }
+};
+struct RunsInArguments {
+    const InlineRuns &r;
+    __device__ __forceinline__ kvx_run at(uint32_t e) const { return r.run[e]; }
+};
+
+template <int T, int U, int NT, typename Runs>
+__device__ __forceinline__ void copy_tiles(const Runs &runs, const char *__restrict__ src, char *__restrict__ dst,
+                                           const CopyParams &p) {
     constexpr uint32_t kStep = T * 16u; // bytes one load instruction of the workgroup covers
     constexpr uint32_t kTile = kStep * U;
     const uint32_t lane_off = threadIdx.x * 16u;
@@ -437,7 +448,7 @@ __global__ __launch_bounds__(T) void copy_kernel(const kvx_run *__restrict__ run
         lc += p.lc_first;
         // the whole 32-byte record in one scalar load (field by field the compiler fetches it in three
         // dependent steps, each a round trip to the scalar cache or beyond)
-        const kvx_run run = load_run(runs + e);
+        const kvx_run run = runs.at(e);
         const uint32_t base = s * kTile;
         if (base >= run.bytes) continue;
         const uint32_t rem = run.bytes - base;
@@ -471,6 +482,20 @@ __global__ __launch_bounds__(T) void copy_kernel(const kvx_run *__restrict__ run
         }
     }
 }
+
+template <int T, int U, int NT>
+__global__ __launch_bounds__(T) void copy_kernel(const kvx_run *__restrict__ runs, const char *__restrict__ src,
+                                                 char *__restrict__ dst, CopyParams p) {
+    copy_tiles<T, U, NT>(RunsInMemory{runs}, src, dst, p);
+}
+
+// The same with the run records inside the launch arguments: no table in device memory, no planning launch.
+template <int T, int U, int NT>
+__global__ __launch_bounds__(T) void copy_inline_kernel(InlineRuns runs, const char *__restrict__ src,
+                                                        char *__restrict__ dst, CopyParams p) {
+    copy_tiles<T, U, NT>(RunsInArguments{runs}, src, dst, p);
+}
+static_assert(sizeof(InlineRuns) + sizeof(CopyParams) + 2 * sizeof(void *) <= 4096, "launch arguments are limited to 4 KiB");
 
 // ---------------------------------------------------------------------------
 // xpose: pages that are not [token][head][dim] inside
@@ -917,41 +942,58 @@ hipError_t launch_fill(const FillParams &p, hipStream_t stream) {
 
 namespace {
 
+// Lets kernel `fn` reserve all of a compute unit's LDS.  The attribute is sticky, per kernel instance and per
+// device: `raised_on` (one per instance) remembers the devices where it has been set.
+inline hipError_t raise_lds_limit(const void *fn, std::atomic<uint64_t> &raised_on) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = dev >= 0 && dev < 64 ? 1ull << dev : 0;
+    if (!(raised_on.load(std::memory_order_relaxed) & bit) || !bit) {
+        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
+        if (e != hipSuccess) return e;
+        raised_on.fetch_or(bit, std::memory_order_relaxed);
+    }
+    return hipSuccess;
+}
+
 // Dispatch of the runtime (threads, unroll, nontemporal) triple to a template instance.
 // `lds` bytes of dynamic LDS are reserved and never touched: they only cap the workgroups per compute unit.
 template <int T, int U, int NT>
-hipError_t copy_tun(const CopyParams &p, uint32_t grid, uint32_t lds, hipStream_t stream) {
-    if (lds > 64u * 1024u) {
-        // The attribute is sticky, per kernel instance and per device: remember where it has been raised.
-        static std::atomic<uint64_t> raised_on{0};
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e != hipSuccess) return e;
-        const uint64_t bit = dev >= 0 && dev < 64 ? 1ull << dev : 0;
-        if (!(raised_on.load(std::memory_order_relaxed) & bit) || !bit) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&copy_kernel<T, U, NT>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu);
+hipError_t copy_tun(const CopyParams &p, const InlineRuns *inline_runs, uint32_t grid, uint32_t lds,
+                    hipStream_t stream) {
+    if (inline_runs) {
+        if (lds > 64u * 1024u) {
+            static std::atomic<uint64_t> raised_on{0};
+            const hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(&copy_inline_kernel<T, U, NT>), raised_on);
             if (e != hipSuccess) return e;
-            raised_on.fetch_or(bit, std::memory_order_relaxed);
         }
+        KVX_LAUNCH((copy_inline_kernel<T, U, NT>), dim3(grid), dim3(T), lds, stream, *inline_runs, p.src, p.dst, p);
+        return hipGetLastError();
+    }
+    if (lds > 64u * 1024u) {
+        static std::atomic<uint64_t> raised_on{0};
+        const hipError_t e = raise_lds_limit(reinterpret_cast<const void *>(&copy_kernel<T, U, NT>), raised_on);
+        if (e != hipSuccess) return e;
     }
     KVX_LAUNCH((copy_kernel<T, U, NT>), dim3(grid), dim3(T), lds, stream, p.runs, p.src, p.dst, p);
     return hipGetLastError();
 }
 
 template <int T, int U>
-hipError_t copy_tu(const CopyParams &p, int nt, uint32_t grid, uint32_t lds, hipStream_t stream) {
-    if (nt == 2) return copy_tun<T, U, 2>(p, grid, lds, stream);
-    return nt == 1 ? copy_tun<T, U, 1>(p, grid, lds, stream) : copy_tun<T, U, 0>(p, grid, lds, stream);
+hipError_t copy_tu(const CopyParams &p, const InlineRuns *ir, int nt, uint32_t grid, uint32_t lds, hipStream_t stream) {
+    if (nt == 2) return copy_tun<T, U, 2>(p, ir, grid, lds, stream);
+    return nt == 1 ? copy_tun<T, U, 1>(p, ir, grid, lds, stream) : copy_tun<T, U, 0>(p, ir, grid, lds, stream);
 }
 
 template <int T>
-hipError_t copy_t(const CopyParams &p, uint32_t unroll, int nt, uint32_t grid, uint32_t lds, hipStream_t stream) {
+hipError_t copy_t(const CopyParams &p, const InlineRuns *ir, uint32_t unroll, int nt, uint32_t grid, uint32_t lds,
+                  hipStream_t stream) {
     switch (unroll) {
-    case 1: return copy_tu<T, 1>(p, nt, grid, lds, stream);
-    case 2: return copy_tu<T, 2>(p, nt, grid, lds, stream);
-    case 4: return copy_tu<T, 4>(p, nt, grid, lds, stream);
-    case 8: return copy_tu<T, 8>(p, nt, grid, lds, stream);
+    case 1: return copy_tu<T, 1>(p, ir, nt, grid, lds, stream);
+    case 2: return copy_tu<T, 2>(p, ir, nt, grid, lds, stream);
+    case 4: return copy_tu<T, 4>(p, ir, nt, grid, lds, stream);
+    case 8: return copy_tu<T, 8>(p, ir, nt, grid, lds, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -982,15 +1024,16 @@ hipError_t plain_t(char *dst, const char *src, uint64_t bytes, uint32_t unroll, 
 
 } // namespace
 
-hipError_t launch_copy(const CopyParams &p, uint32_t threads, uint32_t unroll, int nontemporal, uint32_t grid,
-                       uint32_t lds_bytes, hipStream_t stream) {
+hipError_t launch_copy(const CopyParams &p, const InlineRuns *inline_runs, uint32_t threads, uint32_t unroll,
+                       int nontemporal, uint32_t grid, uint32_t lds_bytes, hipStream_t stream) {
     if (p.total_tiles == 0 || grid == 0) return hipSuccess;
+    if (inline_runs && p.num_runs > kInlineRuns) return hipErrorInvalidValue;
     switch (threads) {
-    case 64: return copy_t<64>(p, unroll, nontemporal, grid, lds_bytes, stream);
-    case 128: return copy_t<128>(p, unroll, nontemporal, grid, lds_bytes, stream);
-    case 256: return copy_t<256>(p, unroll, nontemporal, grid, lds_bytes, stream);
-    case 512: return copy_t<512>(p, unroll, nontemporal, grid, lds_bytes, stream);
-    case 1024: return copy_t<1024>(p, unroll, nontemporal, grid, lds_bytes, stream);
+    case 64: return copy_t<64>(p, inline_runs, unroll, nontemporal, grid, lds_bytes, stream);
+    case 128: return copy_t<128>(p, inline_runs, unroll, nontemporal, grid, lds_bytes, stream);
+    case 256: return copy_t<256>(p, inline_runs, unroll, nontemporal, grid, lds_bytes, stream);
+    case 512: return copy_t<512>(p, inline_runs, unroll, nontemporal, grid, lds_bytes, stream);
+    case 1024: return copy_t<1024>(p, inline_runs, unroll, nontemporal, grid, lds_bytes, stream);
     default: return hipErrorInvalidValue;
     }
 }

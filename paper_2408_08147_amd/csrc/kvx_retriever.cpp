@@ -112,13 +112,32 @@ kvx_status kvx_retriever_scatter(kvx_retriever_t *ret, uint32_t slot, const kvx_
     if (!ret || slot >= ret->slots.size() || !d || !db || !dst_pool) return KVX_ERR_INVALID_ARG;
     Slot &s = ret->slots[slot];
     if (s.state != SLOT_ACQUIRED) return KVX_ERR_INVALID_ARG;
-    size_t ws_need = 0;
-    kvx_status st = kvx_plan_workspace_bytes(nullptr, nullptr, d, db, &ws_need);
-    if (st != KVX_OK) return st;
-    if (ws_need > ret->ws_bytes) return KVX_ERR_CAPACITY;
+    kvx_status st = KVX_OK;
     kvx_plan_t *plan = nullptr;
-    st = kvx_plan(nullptr, nullptr, d, db, layer_begin, layer_end, s.ws, ret->ws_bytes, s.stream, &plan);
-    if (st != KVX_OK) return st;
+    // A small arrival (a request or a few) is planned on the host, without the slot's workspace: its run
+    // records ride in the launch arguments, and the scatter below is the only launch.
+    uint64_t pages = db->num_requests;
+    if (db->seq_lens && d->page_tokens)
+        for (uint32_t r = 0; r < db->num_requests && pages <= KVX_INLINE_RUNS; ++r)
+            pages += db->seq_lens[r] / d->page_tokens; // ceil(len/P) <= 1 + len/P, the 1 counted above
+    if (pages <= KVX_INLINE_RUNS) {
+        st = kvx_plan(nullptr, nullptr, d, db, layer_begin, layer_end, nullptr, 0, s.stream, &plan);
+        if (st != KVX_OK) return st;
+        int runs = 0;
+        (void)kvx_plan_can_launch(plan, &runs);
+        if (!runs) { // pages that are not token rows inside: planned on the device like any larger arrival
+            kvx_plan_destroy(plan);
+            plan = nullptr;
+        }
+    }
+    if (!plan) {
+        size_t ws_need = 0;
+        st = kvx_plan_workspace_bytes(nullptr, nullptr, d, db, &ws_need);
+        if (st != KVX_OK) return st;
+        if (ws_need > ret->ws_bytes) return KVX_ERR_CAPACITY;
+        st = kvx_plan(nullptr, nullptr, d, db, layer_begin, layer_end, s.ws, ret->ws_bytes, s.stream, &plan);
+        if (st != KVX_OK) return st;
+    }
     uint64_t total = 0;
     (void)kvx_plan_total_bytes(plan, &total);
     if (total > ret->buf_bytes) {

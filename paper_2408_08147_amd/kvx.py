@@ -24,7 +24,7 @@ OP_PACK, OP_UNPACK, OP_CONVERT = 0, 1, 2
 EXPORTS = (
     "kvx_plan_workspace_bytes", "kvx_plan", "kvx_plan_destroy", "kvx_plan_total_bytes",
     "kvx_plan_segment", "kvx_plan_request_segment", "kvx_plan_get_tables", "kvx_plan_set_launch",
-    "kvx_plan_get_launch", "kvx_pack", "kvx_unpack", "kvx_convert", "kvx_pack_layers",
+    "kvx_plan_get_launch", "kvx_plan_can_launch", "kvx_pack", "kvx_unpack", "kvx_convert", "kvx_pack_layers",
     "kvx_unpack_layers", "kvx_convert_layers", "kvx_pack_blockwise", "kvx_copy_yardstick",
     "kvx_retriever_arena_bytes", "kvx_retriever_create", "kvx_retriever_destroy", "kvx_retriever_acquire",
     "kvx_retriever_scatter", "kvx_retriever_abandon", "kvx_retriever_poll", "kvx_retriever_drain",
@@ -32,6 +32,7 @@ EXPORTS = (
     "kvx_last_device_error",
 )
 NOALLOC_MAX_TABLE_WORDS = 896
+INLINE_RUNS = 96
 NOALLOC_SCRATCH_BYTES = 65536
 
 
@@ -145,6 +146,7 @@ def load():
     lib.kvx_plan_get_tables.argtypes = [C.c_void_p, C.POINTER(PlanTables)]
     lib.kvx_plan_set_launch.argtypes = [C.c_void_p, C.POINTER(LaunchCfg)]
     lib.kvx_plan_get_launch.argtypes = [C.c_void_p, C.POINTER(LaunchCfg)]
+    lib.kvx_plan_can_launch.argtypes = [C.c_void_p, C.POINTER(C.c_int)]
     lib.kvx_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]
     lib.kvx_unpack.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
     lib.kvx_convert.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -267,6 +269,12 @@ def kvx_plan_set_launch(plan: Plan, unroll: int = 0, nontemporal: int = 0, order
     cfg = LaunchCfg(unroll, nontemporal, order, xcd_swizzle, max_workgroups, threads, workgroups_per_cu,
                     xcd_block_tiles)
     _check(load().kvx_plan_set_launch(plan.handle, C.byref(cfg)), "kvx_plan_set_launch")
+
+
+def kvx_plan_can_launch(plan: Plan) -> bool:
+    out = C.c_int(0)
+    _check(load().kvx_plan_can_launch(plan.handle, C.byref(out)), "kvx_plan_can_launch")
+    return bool(out.value)
 
 
 def kvx_plan_get_launch(plan: Plan) -> LaunchCfg:

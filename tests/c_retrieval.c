@@ -1,7 +1,8 @@
 /* Asynchronous retrieval (paper section 3.6) driven from plain C, no Python in the loop: requests arrive one
  * after another (or a few at a time), each is gathered out of the sender's pool into a free receive slot
  * (sender plan + kvx_pack on the slot's stream, standing in for the bytes arriving), scattered from there
- * into the receiver's pool (kvx_retriever_scatter), and reported by kvx_retriever_poll.  Prints the host
+ * into the receiver's pool (kvx_retriever_scatter), and reported by kvx_retriever_poll.  Arrivals of at most
+ * KVX_INLINE_RUNS pages are planned on the host on both sides: one launch to gather, one to scatter.  Prints the host
  * wall time per request for every (slots, requests per arrival) pair asked for, and checks rows of the
  * receiver's pool against the sender's through both block tables.
  *
@@ -146,8 +147,17 @@ int main(int argc, char **argv) {
                         kvx_batch_desc sb = {r1 - r0, 0, lens + r0, perm_s + offs[r0], group_offs};
                         kvx_batch_desc db = {r1 - r0, 0, lens + r0, perm_d + offs[r0], group_offs};
                         kvx_plan_t *plan = NULL;
-                        CHECK_KVX(kvx_plan(&pool, &sb, NULL, NULL, 0, L, d_send_ws + (uint64_t)slot * ((slot_ws + 255) / 256 * 256),
-                                           slot_ws, stream, &plan));
+                        uint64_t pages = offs[r1] - offs[r0];
+                        int runs_inline = 0;
+                        if (pages <= KVX_INLINE_RUNS) { /* planned on the host: the pack is the only launch */
+                            CHECK_KVX(kvx_plan(&pool, &sb, NULL, NULL, 0, L, NULL, 0, stream, &plan));
+                            CHECK_KVX(kvx_plan_can_launch(plan, &runs_inline));
+                            if (!runs_inline) kvx_plan_destroy(plan);
+                        }
+                        if (!runs_inline)
+                            CHECK_KVX(kvx_plan(&pool, &sb, NULL, NULL, 0, L,
+                                               d_send_ws + (uint64_t)slot * ((slot_ws + 255) / 256 * 256), slot_ws, stream,
+                                               &plan));
                         CHECK_KVX(kvx_pack(plan, d_src, buf, slot_buf, stream));
                         kvx_plan_destroy(plan);
                         CHECK_KVX(kvx_retriever_scatter(ret, slot, &pool, &db, 0, L, d_dst, NULL));

@@ -1,6 +1,7 @@
 // Host-only fuzz driver for the validation and plan arithmetic of libkvx, built with
 // AddressSanitizer and UndefinedBehaviorSanitizer on the host side (tests/test_host_sanitizers.py).
-// It never launches a kernel: every plan is host-only (no device workspace).
+// It never launches a kernel: every plan is host-only (no device workspace), and the ones that could launch
+// all the same (small one-sided plans, whose run records the host builds) are only inspected.
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
@@ -43,8 +44,14 @@ static int check_fast_div() {
 
 int main(int argc, char **argv) {
     const int iters = argc > 1 ? atoi(argv[1]) : 20000;
+    int devices = 0;
+    if (hipGetDeviceCount(&devices) == hipSuccess && devices > 0) {
+        // the calls below hand host addresses to entry points that would launch with them
+        printf("a GPU is present: this driver only runs where nothing can be launched\n");
+        return 77;
+    }
     if (check_fast_div()) return 1;
-    long ok = 0, rejected = 0;
+    long ok = 0, rejected = 0, inline_plans = 0;
     for (int it = 0; it < iters; ++it) {
         kvx_pool_desc s{}, d{};
         const uint32_t elems[] = {1, 2, 4, 3, 8};
@@ -149,9 +156,49 @@ int main(int argc, char **argv) {
         cfg.unroll = below(10);
         cfg.threads = 64u << below(6);
         (void)kvx_plan_set_launch(plan, &cfg);
-        if (kvx_pack(plan, &s, &d, total, nullptr) == KVX_OK && total) { printf("host-only plan launched\n"); return 1; }
+        int can = 0;
+        if (kvx_plan_can_launch(plan, &can) != KVX_OK) return 1;
+        if (can) {
+            // one side, token rows, few pages: the host worked the run records out itself.  Every token of every
+            // request must lie in exactly the record its page gives it, at the addresses the geometry defines.
+            if (mode == 2 || !plan->inline_runs) { printf("a plan without run records says it can launch\n"); return 1; }
+            ++inline_plans;
+            const kvx::Geometry &g = mode == 0 ? plan->s : plan->d;
+            const std::vector<uint32_t> &ids = mode == 0 ? ids_s : ids_d;
+            const std::vector<uint64_t> &offs = mode == 0 ? offs_s : offs_d;
+            const uint32_t P = g.desc.page_tokens;
+            const uint64_t row = plan->row, bpt = 2ull * (l1 - l0) * row;
+            uint64_t first = 0, tokens_before = 0;
+            for (uint32_t r = 0; r < R; ++r) {
+                for (uint32_t t = 0; t < lens[r]; ++t) {
+                    const kvx_run &run = plan->inline_runs->run[first + t / P];
+                    const uint64_t pool = mode == 0 ? run.src_off : run.dst_off, buf = mode == 0 ? run.dst_off : run.src_off;
+                    const uint64_t in_run = (uint64_t)(t - run.token) * row;
+                    if (run.request != r || run.seq_len != lens[r] || run.token > t || in_run + row > run.bytes ||
+                        run.token / P != t / P ||
+                        pool + in_run != ids[offs[r] + t / P] * g.sp + (uint64_t)(t % P) * g.token_step ||
+                        buf + in_run != tokens_before * bpt + (uint64_t)t * row) {
+                        printf("host-built run record is wrong (request %u token %u)\n", r, t);
+                        return 1;
+                    }
+                }
+                first += (lens[r] + P - 1) / P;
+                tokens_before += lens[r];
+            }
+            if (first == 0 || first > KVX_INLINE_RUNS) { printf("run records for %llu pages\n", (unsigned long long)first); return 1; }
+            // a run ends with its page or its request: no two records may claim the same token
+            for (uint64_t i = 0; i < first; ++i) {
+                const kvx_run &run = plan->inline_runs->run[i];
+                if (run.bytes == 0 || run.bytes % row || run.token % P || run.token + run.bytes / row > run.seq_len ||
+                    run.bytes / row > P) { printf("host-built run %llu has a bad extent\n", (unsigned long long)i); return 1; }
+            }
+        } else if (kvx_pack(plan, &s, &d, total, nullptr) == KVX_OK && total) {
+            // (a plan that can launch is never handed these host addresses)
+            printf("host-only plan launched\n");
+            return 1;
+        }
         kvx_plan_destroy(plan);
     }
-    printf("fuzz done: %ld plans accepted, %ld rejected\n", ok, rejected);
-    return ok > 100 && rejected > 100 ? 0 : 2;
+    printf("fuzz done: %ld plans accepted (%ld with host-built runs), %ld rejected\n", ok, inline_plans, rejected);
+    return ok > 100 && rejected > 100 && inline_plans > 20 ? 0 : 2;
 }

@@ -137,14 +137,36 @@ def test_workload_5_scaled():
 
 
 # ------------------------------------------------------------------ the device-built plan itself
+def plan_table_lens(rng, batch, Ps, Pd):
+    if batch == "staged":                  # more requests than one scan pass holds; tables copied from pinned memory
+        lens = rng.integers(0, 900, size=1500).astype(np.uint32)
+        lens[::97] = 0
+        return lens
+    # batches whose tables ride in the launch arguments (lengths + both sides' page ids <= 896 words): one
+    # launch plans them, with 1, 4 or 16 waves
+    count = {"one": 1, "four": 4, "five": 5, "sixty_four": 64, "sixty_five": 65, "three_hundred": 300}[batch]
+    pages_each = (896 - count) // count    # pages a request may use on both sides together
+    if pages_each >= 4:
+        hi = int((pages_each - 2) / (1.0 / Ps + 1.0 / Pd))     # ceil() on either side costs at most one page
+    else:
+        hi = min(Ps, Pd)                   # one page per side; the empty requests below make the room
+    lens = rng.integers(1, hi + 1, size=count).astype(np.uint32)
+    if count > 4:
+        lens[1::7] = 0
+    return lens
+
+
+@pytest.mark.parametrize("batch", ["staged", "one", "four", "five", "sixty_four", "sixty_five", "three_hundred"])
 @pytest.mark.parametrize("Ps,Pd", [(16, 16), (128, 16), (5, 7)])
-def test_device_plan_tables(Ps, Pd):
+def test_device_plan_tables(Ps, Pd, batch):
     """The prefix scans and run records the kernels wrote: T_r is the exclusive
     sum of lengths, and per operation the runs of a request tile its tokens
     exactly once, in order, each run inside one page on both sides."""
-    rng = np.random.default_rng(Ps + Pd)
-    lens = rng.integers(0, 900, size=1500).astype(np.uint32)      # more requests than one scan pass holds
-    lens[::97] = 0
+    rng = np.random.default_rng(Ps + Pd + len(batch))
+    lens = plan_table_lens(rng, batch, Ps, Pd)
+    if batch != "staged":
+        pages = lambda q: int(np.sum((lens.astype(np.int64) + q - 1) // q))
+        assert len(lens) + pages(Ps) + pages(Pd) <= kvx.NOALLOC_MAX_TABLE_WORDS, "meant to fit the launch arguments"
     case = G.make_case(rng, 2, 1, 16, 1, lens, Ps, Pd, LM, PM)
     src = np.zeros(case.pool_bytes(case.s), dtype=np.uint8)
     res = G.run_gpu(case, src, 0, 2, want_tables=True)
@@ -207,6 +229,8 @@ ONE_SIDED = {
     # tables in the plan kernel's launch arguments
     "one_request": [16 * 20 - 7],
     "four_requests": [100, 0, 33, 16],
+    "six_requests": [50, 7, 0, 160, 16, 1],
+    "forty_requests": [3 * k % 41 for k in range(40)],
     "sixty_five_requests": [9] * 65,
     "one_request_895_pages": [16 * 895 - 1],        # 1 + 895 words: the most the launch arguments take
     # tables staged in pinned memory and copied

@@ -11,6 +11,7 @@ import pytest
 from oracle import kvxo
 from paper_2408_08147_amd import kvx
 from paper_2408_08147_amd import workloads as W
+from tests import gpu_util as G
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -219,6 +220,58 @@ def test_host_only_plan_cannot_launch():
     expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan_get_tables, p)
     expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan_segment, p, 2, 0)
     expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan_segment, p, 0, 2)
+
+
+def test_small_one_sided_plans_without_a_workspace_can_launch():
+    """One side, token-row pages, at most KVX_INLINE_RUNS used pages: the host builds the run records, and
+    the plan says so."""
+    hdr = open(os.path.join(ROOT, "include", "kvx.h")).read()
+    assert int(re.search(r"#define KVX_INLINE_RUNS (\d+)u", hdr).group(1)) == kvx.INLINE_RUNS == 96
+    s, b = _simple()
+    for p in (kvx.kvx_plan(s, b, None, None, 0, 2), kvx.kvx_plan(None, None, s, b, 1, 2)):
+        assert kvx.kvx_plan_can_launch(p)
+        expect(kvx.ERR_INVALID_ARG, kvx.kvx_convert, p, 4096, 8192)
+        expect(kvx.ERR_INVALID_ARG, kvx.kvx_plan_get_tables, p)
+    p = kvx.kvx_plan(s, b, None, None, 0, 2)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_unpack, p, 4096, 1 << 40, 8192)     # the side it does not have
+    expect(kvx.ERR_CAPACITY, kvx.kvx_pack, p, 4096, 8192, 10)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_pack, p, 0, 8192, 1 << 40)
+    expect(kvx.ERR_ALIGNMENT, kvx.kvx_pack, p, 4096 + 8, 8192, 1 << 40)
+    expect(kvx.ERR_INVALID_ARG, kvx.kvx_pack_layers, p, 1, 3, 4096, 8192, 1 << 40)
+    s96, b96 = _simple(n=(16 * 90, 16 * 6 - 1), NP=200)
+    assert kvx.kvx_plan_can_launch(kvx.kvx_plan(s96, b96, None, None, 0, 2))
+
+
+@pytest.mark.parametrize("what", ["ninety_seven_pages", "two_sided", "head_major_pages", "padded_rows", "empty"])
+def test_plans_without_a_workspace_that_cannot_run(what):
+    """Everything else without a workspace answers the size queries and refuses to launch, before any device
+    call: the pointers handed over here are never touched."""
+    rng = np.random.default_rng(11)
+    lens = {"ninety_seven_pages": [16 * 96 + 1], "empty": [0, 0]}.get(what, [100, 40])
+    inner = 1 if what == "head_major_pages" else 0
+    case = G.make_case(rng, 2, 2, 16, 2, lens, 16, 16, 0, 0, inner_s=inner, inner_d=inner)
+    sp, sb = case.kvx_pool(case.s), kvx.BatchDesc(case.seq_lens, case.ids_s, case.offs_s)
+    dp, db = case.kvx_pool(case.d), kvx.BatchDesc(case.seq_lens, case.ids_d, case.offs_d)
+    if what == "padded_rows":
+        st = case.row + 16                 # layer, K|V, page, token
+        strides = (2 * st * 16 * case.s.num_pages, st * 16 * case.s.num_pages, st * 16, st)
+        sp = kvx.pool_desc(2, 2, 16, 2, 16, case.s.num_pages, 0, strides, 0)
+    if what == "two_sided":
+        plans = [kvx.kvx_plan(sp, sb, dp, db, 0, 2)]
+    else:
+        plans = [kvx.kvx_plan(sp, sb, None, None, 0, 2)]
+        if what != "padded_rows":
+            plans.append(kvx.kvx_plan(None, None, dp, db, 0, 2))
+    for p in plans:
+        assert not kvx.kvx_plan_can_launch(p)
+        if what != "empty":
+            with pytest.raises(kvx.KvxError) as e:
+                kvx.kvx_pack(p, 4096, 8192, 1 << 40)
+            assert e.value.status == kvx.ERR_INVALID_ARG
+            with pytest.raises(kvx.KvxError) as e:
+                kvx.kvx_unpack(p, 4096, 1 << 40, 8192)
+            assert e.value.status == kvx.ERR_INVALID_ARG
+        p.destroy()
 
 
 def test_launch_config_round_trip():

@@ -5,6 +5,8 @@ random, partly malformed descriptors and block tables."""
 import os
 import subprocess
 
+import pytest
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
@@ -23,5 +25,7 @@ def test_host_validation_under_asan_ubsan(tmp_path):
     assert build.returncode == 0, build.stderr[-3000:]
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
     run = subprocess.run([str(exe), "20000"], capture_output=True, text=True, env=env, timeout=300)
+    if run.returncode == 77:
+        pytest.skip("a GPU is present: the driver hands host addresses to launch paths and runs only without one")
     assert run.returncode == 0, (run.stdout[-2000:], run.stderr[-4000:])
     assert "fuzz done" in run.stdout
