@@ -174,7 +174,10 @@ def study_retrieval(args):
                     except kvx.KvxError:
                         break
                     submitted_at[pending.pop(0)] = time.perf_counter()
-                    plan = kvx.kvx_plan(sp, sb, None, None, 0, L, send_ws[slot].data_ptr(), 1 << 16, stream)
+                    plan = kvx.kvx_plan(sp, sb, None, None, 0, L)      # planned on the host when small enough
+                    if not kvx.kvx_plan_can_launch(plan):
+                        plan.destroy()
+                        plan = kvx.kvx_plan(sp, sb, None, None, 0, L, send_ws[slot].data_ptr(), 1 << 16, stream)
                     kvx.kvx_pack(plan, src.data_ptr(), buf_ptr, slot_buf, stream)
                     plan.destroy()
                     kvx.kvx_retriever_scatter(ret, slot, dp, db, 0, L, dst.data_ptr())
