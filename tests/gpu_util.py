@@ -144,6 +144,42 @@ def run_gpu(case: Case, src: np.ndarray, l0: int, l1: int, launch: Optional[dict
     return res
 
 
+def run_gpu_one_sided(case: Case, src: np.ndarray, l0: int, l1: int, launch: Optional[dict] = None):
+    """Pack through a sender-only plan, unpack through a receiver-only plan, as two machines would.  Each plan
+    is made without a workspace when it can run that way (its run records then ride in the launch arguments),
+    else with one.  Returns (total, buf, dst, how) with how = which of the two plans ran without a workspace."""
+    import torch
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream(device=dev)
+    sides = ((case.kvx_pool(case.s), kvx.BatchDesc(case.seq_lens, case.ids_s, case.offs_s)),
+             (case.kvx_pool(case.d), kvx.BatchDesc(case.seq_lens, case.ids_d, case.offs_d)))
+    plans, keep, how = [], [], []
+    with torch.cuda.stream(stream):
+        for k, (pool, batch) in enumerate(sides):
+            args = (pool, batch, None, None) if k == 0 else (None, None, pool, batch)
+            plan = kvx.kvx_plan(*args, l0, l1)
+            how.append(kvx.kvx_plan_can_launch(plan))
+            if not how[-1]:
+                plan.destroy()
+                ws = torch.zeros(kvx.kvx_plan_workspace_bytes(*args), dtype=torch.uint8, device=dev)
+                keep.append(ws)
+                plan = kvx.kvx_plan(*args, l0, l1, ws.data_ptr(), ws.numel(), stream.cuda_stream)
+            if launch:
+                kvx.kvx_plan_set_launch(plan, **launch)
+            plans.append(plan)
+        total = kvx.kvx_plan_total_bytes(plans[0])
+        assert total == kvx.kvx_plan_total_bytes(plans[1])
+        src_t = torch.from_numpy(src).to(dev)
+        buf = torch.full((total + BUF_SLACK,), CANARY_BUF, dtype=torch.uint8, device=dev)
+        dst = torch.full((case.pool_bytes(case.d),), CANARY_POOL, dtype=torch.uint8, device=dev)
+        kvx.kvx_pack(plans[0], src_t.data_ptr(), buf.data_ptr(), total, stream.cuda_stream)
+        kvx.kvx_unpack(plans[1], buf.data_ptr(), total, dst.data_ptr(), stream.cuda_stream)
+    stream.synchronize()
+    for plan in plans:
+        plan.destroy()
+    return total, buf.cpu().numpy(), dst.cpu().numpy(), tuple(how)
+
+
 def assert_same(got: Result, want: Result, what: str = ""):
     assert got.total == want.total, what
     for name in ("buf", "dst_unpack", "dst_convert"):

@@ -60,3 +60,32 @@ def test_random_case_with_token_innermost_pages(seed):
     want = G.run_oracle(case, src, l0, l1)
     got = G.run_gpu(case, src, l0, l1, launch=launch)
     G.assert_same(got, want, f"seed {seed} layers [{l0},{l1}) launch {launch}")
+
+
+HOST_PLANNED = {"seeds": 0, "sender": 0, "receiver": 0}
+
+
+@pytest.mark.parametrize("seed", range(1000, 1300))
+def test_random_case_one_sided_plans(seed):
+    """The same cases as two machines see them: a sender-only plan for the pack, a receiver-only plan for the
+    unpack, each without a workspace where that is allowed (run records built on the host)."""
+    case, (l0, l1), launch, rng = draw_case(seed)
+    src = rng.integers(0, 256, size=case.pool_bytes(case.s), dtype=np.uint8)
+    want = G.run_oracle(case, src, l0, l1)
+    total, buf, dst, how = G.run_gpu_one_sided(case, src, l0, l1, launch=launch)
+    what = f"seed {seed} layers [{l0},{l1}) launch {launch} without workspace {how}"
+    assert total == want.total, what
+    assert np.array_equal(buf, want.buf), what
+    assert np.array_equal(dst, want.dst_unpack), what
+    HOST_PLANNED["seeds"] += 1
+    HOST_PLANNED["sender"] += how[0]
+    HOST_PLANNED["receiver"] += how[1]
+
+
+def test_random_cases_did_cover_both_kinds_of_one_sided_plans():
+    """Runs after the 300 cases above (same file, collected in order): a good share of them were planned on
+    the host, and a good share on the device."""
+    if HOST_PLANNED["seeds"] < 300:
+        pytest.skip("only meaningful after the whole list has run in this process")
+    for side in ("sender", "receiver"):
+        assert 30 <= HOST_PLANNED[side] <= 270, HOST_PLANNED
