@@ -143,8 +143,8 @@ typedef struct {
                                2 = non-temporal loads and stores, 3 = non-temporal loads with agent-scope
                                (write-through) stores */
     uint32_t order;         /* 0 = chosen per operation (pack: 3, with fewer than 64 runs 1; unpack and convert: 2
-                               into a page-major receiver, else 1), 1 = (layer,kv) outermost, 2 = copy run (for convert: group of
-                               runs) outermost, 3 = the runs cut into eight parts, one per XCD, each part walked
+                               into a page-major receiver, else 1), 1 = (layer,kv) outermost, 2 = copy run (for a convert into
+                               coarser pages: the runs of one receiver page) outermost, 3 = the runs cut into eight parts, one per XCD, each part walked
                                with (layer,kv) outermost ([token][head][dim] pages only, else as 1) */
     uint32_t xcd_swizzle;   /* 1 = off, 2 = give each of the 8 XCDs contiguous tiles: one eighth of the grid
                                each, or blocks of `xcd_block_tiles` tiles dealt round-robin */

@@ -366,8 +366,11 @@ void kvx::default_launch(kvx_launch_cfg *c) {
 namespace {
 
 // Tile shape when the caller left it open.  Measured on MI355X: with (layer,kv) outermost the smallest
-// tile (256 lanes x 16 B) with the largest grid is fastest; with the run group outermost (page-major
-// receiver) one workgroup per whole run, up to 512 lanes x 4 x 16 B = 32 KiB, is.
+// tile (256 lanes x 16 B) with the largest grid is fastest; with the run outermost (page-major receiver)
+// 128 lanes x 4 loads each = 8 KiB tiles, four workgroups to a compute unit (run_op caps them), are: against
+// one 32 KiB tile of 512 lanes per compute unit +2 % on workload 4, +7 % into a page-major pool of workload
+// 2's shape, +2 % of workload 3's, +6 % on an unpack into 128-token pages; four loads per lane matter more
+// than the lanes (one or two loads per lane: 4.6-5.5 TB/s where four give 6.3-6.6).
 // Cache policy when the caller left it open (values as in kvx_launch_cfg, minus one for the kernels).
 // Measured on MI355X: agent-scope stores gain 1-2 % wherever the runs are long (128 KiB and more), into a
 // pool or into the buffer alike, and on a plain copy; they lose up to 8 % where the runs are short.
@@ -380,7 +383,7 @@ namespace {
 // 15.5-19 us per request, 355 MB at a time 15.9 -> 14.5, 1.4 GB 16.3 -> 14.8, 5.7 GB no difference; a
 // 23 GB pack + unpack loses 3.6 % with them.
 constexpr uint64_t kSmallPackBytes = 2ull << 30;
-int resolve_policy(uint32_t nontemporal, bool flat_copy, bool writes_pool, uint32_t max_run_bytes,
+int resolve_policy(uint32_t nontemporal, bool flat_copy, bool writes_pool, uint64_t max_run_bytes,
                    uint64_t launch_bytes) {
     if (nontemporal) return (int)nontemporal - 1;
     if (flat_copy && !writes_pool && launch_bytes <= kSmallPackBytes) return 2;
@@ -391,7 +394,7 @@ void resolve_tile(uint32_t order, uint32_t max_run_bytes, uint32_t *threads, uin
     if (*threads && *unroll) return;
     uint32_t t = 256, u = 1;
     if (order == 2) {
-        t = 512;
+        t = 128;
         while (u < 4 && tile_bytes(t, u * 2) <= max_run_bytes) u *= 2;
     }
     if (!*threads) *threads = t;
@@ -907,7 +910,12 @@ kvx_status kvx::run_op(const kvx_plan_s *plan, Op op, uint32_t lb, uint32_t le, 
         if (op != OP_PACK && !plan->d.custom_strides && plan->d.desc.layout == KVX_LAYOUT_PAGE_MAJOR) cp.order = 2;
         else cp.order = (op == OP_PACK && o.num_runs >= kRunsForParts) ? 3 : 1;
     }
-    cp.group = o.group_slots;
+    // Order 2 keeps `group` consecutive runs together inside one (layer,kv) before it moves to the next.  With
+    // the receiver's pages the coarser ones the runs of a group fill one receiver page, side by side for every
+    // (layer,kv): the whole group it is.  With the receiver's pages the finer ones every run is a receiver page
+    // of its own, whose (layer,kv) pieces lie one behind the other: walking one run through all of them writes
+    // that page front to back (workload 4, 128 -> 16 tokens: 25.1 -> 24.4 ms, three processes).
+    cp.group = (op == OP_CONVERT && plan->d.desc.page_tokens < plan->s.desc.page_tokens) ? 1u : o.group_slots;
     uint32_t threads = c.threads, unroll = c.unroll;
     resolve_tile(cp.order, o.max_run_bytes, &threads, &unroll);
     const uint32_t tile = tile_bytes(threads, unroll);
@@ -937,16 +945,23 @@ kvx_status kvx::run_op(const kvx_plan_s *plan, Op op, uint32_t lb, uint32_t le, 
     cp.by_group = make_fast_div(cp.group);
     cp.by_num_lc = make_fast_div(cp.num_lc);
     cp.by_swizzle_block = make_fast_div(cp.swizzle_block);
-    // Bytes in flight: the large tiles of order 2 fill a compute unit with 128 KiB of loads when as many
-    // workgroups as fit are resident; measured, 32 KiB per compute unit (8 MB over the device, what the
-    // small tiles of the other orders have anyway) is 3 % faster.  Unless the caller chose a tile or a cap.
+    // Bytes in flight: the tiles of order 2 (four loads per lane) fill a compute unit with 128 KiB of loads
+    // when as many workgroups as fit are resident; measured, 32 KiB per compute unit (8 MB over the device,
+    // what the small tiles of the other orders have anyway) is 3 % faster.  Unless the caller chose a tile or
+    // a cap.
     uint32_t per_cu = c.workgroups_per_cu;
-    if (!per_cu && cp.order == 2 && !c.threads && !c.unroll) per_cu = std::max(1u, 32768u / tile);
+    if (!per_cu && cp.order == 2 && !c.threads && !c.unroll) per_cu = std::min(16u, std::max(1u, 32768u / tile));
     const uint64_t launch_bytes = plan->total / (plan->l1 - plan->l0) * (le - lb);
+    // What counts as a long run for the cache policy: in a page-major receiver the (layer,kv) pieces of a
+    // page lie one behind the other, and order 2 writes them in that order, so the stretch written front to
+    // back is all of them (workload 4: 80 x 32 KiB).
+    uint64_t stretch = o.max_run_bytes;
+    if (cp.order == 2 && op != OP_PACK && !plan->d.custom_strides && plan->d.desc.layout == KVX_LAYOUT_PAGE_MAJOR)
+        stretch *= cp.num_lc;
     // with a workspace the table in it is what the kernel reads, as kvx_plan_get_tables promises
     const InlineRuns *inline_runs = plan->ws ? nullptr : plan->inline_runs.get();
     hipError_t e = launch_copy(cp, inline_runs, threads, unroll,
-                               resolve_policy(c.nontemporal, true, op != OP_PACK, o.max_run_bytes, launch_bytes), grid,
+                               resolve_policy(c.nontemporal, true, op != OP_PACK, stretch, launch_bytes), grid,
                                occupancy_lds(per_cu), static_cast<hipStream_t>(stream));
     return hip_ok(e, "copy_kernel launch") ? KVX_OK : KVX_ERR_DEVICE;
 }
