@@ -29,9 +29,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # profiles/ (scaled by the plain-copy calibration).  They are figures of an earlier run, not of this one, and
 # are reported only while the library that runs is built from the very sources they were taken on.
 COUNTER_RUNS = {
-    "build_id": "kvx-sources:bede4354b3672f7e3a0bc7cfef1c620d",
+    "build_id": "kvx-sources:04079a435cb0deab9b15570d90713694",
     "summary": "profiles/copy_kernel_workloads_2_3_5_4.txt",
-    "traffic_bytes_per_launch": {2: 12103913831, 3: 13228422550, 5: 47001769274, 4: 152991547392},
+    "traffic_bytes_per_launch": {2: 12103913367, 3: 13228423321, 5: 47001742400, 4: 152991546100},
 }
 
 

@@ -150,7 +150,7 @@ typedef struct {
                                each, or blocks of `xcd_block_tiles` tiles dealt round-robin */
     uint32_t max_workgroups;/* cap on the grid; tiles beyond it are taken in a grid-stride loop */
     uint32_t threads;       /* lanes per workgroup: 64, 128, 256, 512 or 1024; a tile is threads*16*unroll bytes */
-    uint32_t workgroups_per_cu; /* 0 = as many as fit (with the library's own 32 KiB tiles of order 2: one);
+    uint32_t workgroups_per_cu; /* 0 = as many as fit (with the library's own 8 KiB tiles of order 2: four);
                                n = at most n resident per compute unit (1..8), which bounds the bytes in
                                flight; done by reserving unused LDS per workgroup */
     uint32_t xcd_block_tiles; /* with xcd_swizzle 2: 0 = eighths of the grid, else a power of two */
@@ -408,8 +408,7 @@ kvx_status kvx_copy_yardstick(void *dst, const void *src, uint64_t bytes, const 
  *   - default launch configuration.
  * Two kernel launches on `stream` (the planner, then the unpack) and nothing else, so the call may be recorded while
  * `stream` is being captured into a HIP graph; the first call on a device also asks the runtime for the
- * scratch array's address (and, for a page-major receiver, raises a kernel's LDS limit once), so make one
- * call on the device before capturing.  Every call on a GPU uses that GPU's one
+ * scratch array's address, so make one call on the device before capturing.  Every call on a GPU uses that GPU's one
  * scratch array: it keeps the previous call's tables, each call rewrites everything it reads, and calls
  * on the same stream are ordered; calls that overlap on one GPU (different streams, or threads on
  * different streams) race on the array and must be serialised by the caller. */

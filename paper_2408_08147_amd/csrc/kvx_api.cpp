@@ -752,7 +752,8 @@ kvx_status run_xpose(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t le, co
     xp.order = c.order == 3 ? 1u : c.order; // an eighth of the runs per XCD exists in the flat kernel only
     if (!xp.order)
         xp.order = (op != OP_PACK && !plan->d.custom_strides && plan->d.desc.layout == KVX_LAYOUT_PAGE_MAJOR) ? 2 : 1;
-    xp.group = o.group_slots;
+    // as in run_op: with the receiver's pages the finer ones, one run goes through all its (layer,kv) pieces
+    xp.group = (op == OP_CONVERT && plan->d.desc.page_tokens < plan->s.desc.page_tokens) ? 1u : o.group_slots;
     const uint32_t grid_cap = std::min<uint32_t>(c.max_workgroups, (1u << 31) / kXposeThreads - 8u);
     uint32_t grid = std::min(xp.total_tiles, grid_cap);
     if (c.xcd_swizzle == 2) {
@@ -836,7 +837,7 @@ kvx_status run_xpose_elem(const kvx_plan_t *plan, Op op, uint32_t lb, uint32_t l
     ep.order = c.order == 3 ? 1u : c.order;
     if (!ep.order)
         ep.order = (op != OP_PACK && !gd.custom_strides && gd.desc.layout == KVX_LAYOUT_PAGE_MAJOR) ? 2 : 1;
-    ep.group = o.group_slots;
+    ep.group = o.group_slots; // the runs of one coarse page stay together: their pieces share 128-byte lines
     const uint32_t grid_cap = std::min<uint32_t>(c.max_workgroups, (1u << 31) / kElemThreads - 8u);
     uint32_t grid = std::min(ep.total_tiles, grid_cap);
     if (c.xcd_swizzle == 2) {
