@@ -29,9 +29,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # profiles/ (scaled by the plain-copy calibration).  They are figures of an earlier run, not of this one, and
 # are reported only while the library that runs is built from the very sources they were taken on.
 COUNTER_RUNS = {
-    "build_id": "kvx-sources:04079a435cb0deab9b15570d90713694",
+    "build_id": "kvx-sources:941b7b59d54e3d8ae5b00e9ee1880ee4",
     "summary": "profiles/copy_kernel_workloads_2_3_5_4.txt",
-    "traffic_bytes_per_launch": {2: 12103913367, 3: 13228423321, 5: 47001742400, 4: 152991546100},
+    "traffic_bytes_per_launch": {2: 12103914358, 3: 13228422392, 5: 47001687500, 4: 152991552595},
 }
 
 

@@ -19,6 +19,9 @@
 //                of (run, layer, K|V) and moves them with 16-byte loads and
 //                stores, all loads of a tile in flight before its first store.
 //                No LDS: no byte changes its position inside a 16-byte unit.
+//   copy_inline_kernel  the same data mover with the run records inside its
+//                launch arguments, for a small one-sided plan whose runs the
+//                host worked out: nothing is planned on the device.
 //   xpose_kernel the same three operations for every other page arrangement
 //                (head-major, token axis inside 16-byte dim groups, padded or
 //                sliced rows): tiles of tokens x 16-byte units, staged through
